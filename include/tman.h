@@ -1,0 +1,138 @@
+/*
+ * tman.h -- C ABI of the MI355X (gfx950) table-lookup mixed-precision matmul library.
+ *
+ * The library implements the hot path of T-MAN (arxiv 2511.11248): the product of group-quantized
+ * 1/2/4-bit weights with fp16 activations, y = x * dequant(W)^T, computed through table lookup --
+ * bit-serial activation tables for decoding (mpGEMV) and a two-level table dequantization feeding
+ * the matrix cores for prefill (mpGEMM) -- from ONE bit-serial packed copy of the weights.
+ *
+ * Conventions for every call
+ *   - all data pointers are DEVICE pointers unless stated otherwise; the caller owns every buffer,
+ *     the library never allocates, frees or keeps a pointer after the call returns;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); every call only enqueues
+ *     work on it and never synchronises with the host;
+ *   - tensors are row-major; fp16 means IEEE binary16;
+ *   - the return value is TMAN_OK or a negative tman_status; arguments are validated before
+ *     anything is launched, so an error means no work was enqueued (except TMAN_ERR_LAUNCH, which
+ *     reports the HIP runtime refusing a launch).
+ */
+#ifndef TMAN_H
+#define TMAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum tman_status {
+    TMAN_OK = 0,
+    TMAN_ERR_NULL = -1,      /* a required pointer is NULL */
+    TMAN_ERR_BITS = -2,      /* bits not in {1, 2, 4} */
+    TMAN_ERR_GROUP = -3,     /* group not in {32, 64, 128} */
+    TMAN_ERR_SHAPE = -4,     /* M < 1, K < 1, K % group != 0, N out of range, flags/zeros mismatch */
+    TMAN_ERR_WORKSPACE = -5, /* workspace missing or smaller than the *_workspace_bytes query */
+    TMAN_ERR_ALIGN = -6,     /* a pointer is not 16-byte aligned */
+    TMAN_ERR_LAUNCH = -7     /* the HIP runtime reported an error when launching */
+} tman_status;
+
+#define TMAN_FLAG_HAS_ZERO 1 /* weights carry a per-group zero point (affine form) */
+
+/*
+ * Problem statement (Sec. 4.1: weights (M, K), activations (N, K); Sec. 2.2 for the formats):
+ *   W has M rows (output features) and K columns (input features); code q[m][k] is an unsigned
+ *   integer below 2^bits; along K the codes are grouped in blocks of `group` that share one fp16
+ *   scale and (flag HAS_ZERO) one fp16 zero point.
+ *     HAS_ZERO set:   w[m][k] = (q[m][k] - zero[m][k/group]) * scale[m][k/group]    (Sec. 2.2)
+ *     HAS_ZERO clear: w[m][k] = (2 q[m][k] - 1) * scale[m][k/group]                 (sign plane; bits must be 1)
+ */
+typedef struct tman_shape {
+    int32_t M;
+    int32_t K;
+    int32_t bits;  /* 1, 2 or 4 */
+    int32_t group; /* quantization block size along K: 32, 64 or 128; K % group == 0 */
+    int32_t flags; /* TMAN_FLAG_* */
+} tman_shape_t;
+
+/* Maximum number of tokens one tman_mpgemv call (and one lookup-table buffer) serves. */
+#define TMAN_MAX_DECODE_TOKENS 8
+
+/* Size queries (host only, no GPU needed).  Return 0 for an invalid shape / N. */
+size_t tman_packed_bytes(const tman_shape_t *shape);
+size_t tman_lut_bytes(int32_t N, int32_t K, int32_t group);
+size_t tman_mpgemv_workspace_bytes(const tman_shape_t *shape, int32_t N);
+size_t tman_mpgemm_workspace_bytes(const tman_shape_t *shape, int32_t N);
+
+/*
+ * Offline weight repacking (Sec. 4.1 "Unified Layout": decoding's bit-serial packing is the stored
+ * form, pre-permuted so that both kernels fetch contiguous blocks).
+ *   codes  : uint8 [M][K], one code per byte (bits above `bits` are ignored)
+ *   scales : fp16  [M][K/group]
+ *   zeros  : fp16  [M][K/group], required iff HAS_ZERO, must be NULL otherwise
+ *   packed : tman_packed_bytes(shape) bytes, 16-byte aligned; fully overwritten (padding is zeroed)
+ * The result is position independent (may be copied, saved and reloaded) and starts with a 128-byte
+ * header recording the shape.  Layout: rows in blocks of 32, columns in tiles of 256; inside a tile
+ * block each of 64 lanes (row%32 + 32*half) owns 128 weights of one row, stored as `bits` 16-byte
+ * chunks (one 1024-byte coalesced sub-block per chunk index) whose 32-bit words are single bit-planes
+ * of 32 consecutive weights (weight t of a 4-bit lookup index in bit t, Sec. 4.1 "Bit repacking"),
+ * followed by the lane's group scales/zeros.
+ */
+int tman_pack_weights(const tman_shape_t *shape, const uint8_t *codes, const void *scales, const void *zeros,
+                      void *packed, void *stream);
+
+/* Inverse of tman_pack_weights (test aid and format check): recovers codes [M][K] and, when the
+ * pointers are non-NULL, scales / zeros [M][K/group]. */
+int tman_unpack_weights(const tman_shape_t *shape, const void *packed, uint8_t *codes, void *scales, void *zeros,
+                        void *stream);
+
+/*
+ * Lookup-table precompute (Sec. 2.2 "Bit-serial table lookup"; Sec. 5 "Graph optimization": the
+ * precompute is a call of its own so layers fed by the same activation share one table).
+ *   x   : fp16 [N][K], 1 <= N <= TMAN_MAX_DECODE_TOKENS
+ *   lut : tman_lut_bytes(N, K, group) bytes, 16-byte aligned.  Receives, for every group of 4
+ *         consecutive activations j and every 4-bit pattern p, the fp16 entry
+ *         T[n][j][p] = sum_{t<4, bit t of p set} x[n][4j+t]   (fp32 sum, ascending t, one rounding),
+ *         followed by the fp32 sums S[n][G] of x over each quantization block G of `group` columns
+ *         (used for the zero-point term).  Entries for tokens / columns beyond N / K are zero.
+ * The buffer may be passed to any number of tman_mpgemv calls with the same K and group.
+ */
+int tman_build_lut(const void *x, int32_t N, int32_t K, int32_t group, void *lut, void *stream);
+
+/*
+ * Decoding mpGEMV through table lookup (Sec. 2.2, Sec. 4.3):
+ *   y[n][m] = sum_G scale[m][G] * ( sum_i 2^i sum_{j in G} T[n][j][idx_i[m][j]] - zero[m][G] * S[n][G] )
+ * where idx_i[m][j] is the 4-bit pattern of bit-plane i over weights 4j..4j+3 (sign form:
+ * scale * (2 * sum_j T - S)).  fp16 table entries, fp32 accumulation, fp16 result.
+ *   packed    : from tman_pack_weights for the same shape
+ *   lut       : from tman_build_lut(x, N, shape->K, shape->group)
+ *   y         : fp16 [N][M]
+ *   workspace : tman_mpgemv_workspace_bytes(shape, N) bytes, 16-byte aligned.  It must be zero-filled
+ *               once before its first use; every call leaves it ready for the next one.  Calls that
+ *               may overlap in time need separate workspaces.
+ * Deterministic: the same inputs give bit-identical outputs on every call.
+ */
+int tman_mpgemv(const tman_shape_t *shape, const void *packed, const void *lut, int32_t N, void *y, void *workspace,
+                size_t workspace_bytes, void *stream);
+
+/*
+ * Prefill mpGEMM (Sec. 4.1 "Fused LUT-based dequantization", Sec. 4.2): bit-planes are repacked to
+ * codes (level 1), each code is looked up in its quantization block's table
+ * D[c] = fp16((c - zero) * scale) (level 2; sign form fp16((2c - 1) * scale)), and the fp16 weights
+ * feed the matrix cores with fp32 accumulation.
+ *   x : fp16 [N][K], any N >= 1;   y : fp16 [N][M]
+ *   workspace : tman_mpgemm_workspace_bytes(shape, N) bytes (may be 0, then NULL is accepted)
+ */
+int tman_mpgemm(const tman_shape_t *shape, const void *packed, const void *x, int32_t N, void *y, void *workspace,
+                size_t workspace_bytes, void *stream);
+
+/* Static, human-readable name of a status code. */
+const char *tman_status_string(int status);
+
+/* Layout version of the packed format this build reads and writes (also stored in the header). */
+int32_t tman_layout_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TMAN_H */

@@ -1,0 +1,21 @@
+"""MI355X-native table-lookup mixed-precision matmul (the hot path of T-MAN, arxiv 2511.11248).
+
+Thin binding over the C-ABI library ``libtman.so`` (see ``include/tman.h``): the functions here have
+the same names as the C entry points and only marshal arguments; every step runs in HIP kernels.
+"""
+from .api import (  # noqa: F401
+    Shape,
+    TmanError,
+    library_path,
+    tman_packed_bytes,
+    tman_lut_bytes,
+    tman_mpgemv_workspace_bytes,
+    tman_mpgemm_workspace_bytes,
+    tman_pack_weights,
+    tman_unpack_weights,
+    tman_build_lut,
+    tman_mpgemv,
+    tman_mpgemm,
+    tman_status_string,
+    tman_layout_version,
+)

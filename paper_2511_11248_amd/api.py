@@ -1,0 +1,163 @@
+"""ctypes binding of libtman.so.  Argument marshalling only -- no arithmetic happens in Python.
+
+Tensors are ``torch`` tensors on the GPU (torch supplies device memory and the stream); anything with
+a ``data_ptr()`` works.  Every call enqueues on ``stream`` (default: torch's current stream) and
+returns without synchronising.  A missing library is an error: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtman.so")
+_lib = None
+
+TMAN_FLAG_HAS_ZERO = 1
+TMAN_MAX_DECODE_TOKENS = 8
+
+
+class TmanError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {tman_status_string(status)} (status {status})")
+
+
+class _CShape(C.Structure):
+    _fields_ = [("M", C.c_int32), ("K", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32), ("flags", C.c_int32)]
+
+
+@dataclass(frozen=True)
+class Shape:
+    """Mirror of ``tman_shape_t``: W is (M, K), ``bits``-bit codes, quantization blocks of ``group``
+    along K, with a per-block zero point unless ``has_zero`` is False (1-bit sign form)."""
+    M: int
+    K: int
+    bits: int
+    group: int
+    has_zero: bool = True
+
+    def c(self) -> _CShape:
+        return _CShape(self.M, self.K, self.bits, self.group, TMAN_FLAG_HAS_ZERO if self.has_zero else 0)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2511_11248_amd.build` "
+                "(there is no non-HIP fallback)")
+        L = C.CDLL(_LIB_PATH)
+        sp, vp = C.POINTER(_CShape), C.c_void_p
+        L.tman_packed_bytes.restype = C.c_size_t
+        L.tman_packed_bytes.argtypes = [sp]
+        L.tman_lut_bytes.restype = C.c_size_t
+        L.tman_lut_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.tman_mpgemv_workspace_bytes.restype = C.c_size_t
+        L.tman_mpgemv_workspace_bytes.argtypes = [sp, C.c_int32]
+        L.tman_mpgemm_workspace_bytes.restype = C.c_size_t
+        L.tman_mpgemm_workspace_bytes.argtypes = [sp, C.c_int32]
+        L.tman_pack_weights.restype = C.c_int
+        L.tman_pack_weights.argtypes = [sp, vp, vp, vp, vp, vp]
+        L.tman_unpack_weights.restype = C.c_int
+        L.tman_unpack_weights.argtypes = [sp, vp, vp, vp, vp, vp]
+        L.tman_build_lut.restype = C.c_int
+        L.tman_build_lut.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]
+        L.tman_mpgemv.restype = C.c_int
+        L.tman_mpgemv.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.tman_mpgemm.restype = C.c_int
+        L.tman_mpgemm.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.tman_status_string.restype = C.c_char_p
+        L.tman_status_string.argtypes = [C.c_int]
+        L.tman_layout_version.restype = C.c_int32
+        L.tman_layout_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise TmanError(status, where)
+
+
+def tman_status_string(status: int) -> str:
+    return _load().tman_status_string(status).decode()
+
+
+def tman_layout_version() -> int:
+    return int(_load().tman_layout_version())
+
+
+def tman_packed_bytes(shape: Shape) -> int:
+    return int(_load().tman_packed_bytes(C.byref(shape.c())))
+
+
+def tman_lut_bytes(N: int, K: int, group: int) -> int:
+    return int(_load().tman_lut_bytes(N, K, group))
+
+
+def tman_mpgemv_workspace_bytes(shape: Shape, N: int) -> int:
+    return int(_load().tman_mpgemv_workspace_bytes(C.byref(shape.c()), N))
+
+
+def tman_mpgemm_workspace_bytes(shape: Shape, N: int) -> int:
+    return int(_load().tman_mpgemm_workspace_bytes(C.byref(shape.c()), N))
+
+
+def tman_pack_weights(shape: Shape, codes, scales, zeros, packed, stream=None) -> None:
+    """codes u8 [M][K], scales/zeros fp16 [M][K/group] (zeros None for the sign form) -> packed (u8 blob)."""
+    _check(_load().tman_pack_weights(C.byref(shape.c()), _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(packed),
+                                     _stream(stream)), "tman_pack_weights")
+
+
+def tman_unpack_weights(shape: Shape, packed, codes, scales=None, zeros=None, stream=None) -> None:
+    _check(_load().tman_unpack_weights(C.byref(shape.c()), _ptr(packed), _ptr(codes), _ptr(scales), _ptr(zeros),
+                                       _stream(stream)), "tman_unpack_weights")
+
+
+def tman_build_lut(x, N: int, K: int, group: int, lut, stream=None) -> None:
+    """x fp16 [N][K] -> lut (u8 buffer of tman_lut_bytes(N, K, group))."""
+    _check(_load().tman_build_lut(_ptr(x), N, K, group, _ptr(lut), _stream(stream)), "tman_build_lut")
+
+
+def tman_mpgemv(shape: Shape, packed, lut, N: int, y, workspace, stream=None) -> None:
+    """y fp16 [N][M] = x * dequant(W)^T through table lookup; workspace zero-filled once by the caller."""
+    wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
+    _check(_load().tman_mpgemv(C.byref(shape.c()), _ptr(packed), _ptr(lut), N, _ptr(y), _ptr(workspace), wb,
+                               _stream(stream)), "tman_mpgemv")
+
+
+def tman_mpgemm(shape: Shape, packed, x, N: int, y, workspace=None, stream=None) -> None:
+    """y fp16 [N][M] = x fp16 [N][K] * dequant(W)^T, table dequantization feeding the matrix cores."""
+    wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
+    _check(_load().tman_mpgemm(C.byref(shape.c()), _ptr(packed), _ptr(x), N, _ptr(y), _ptr(workspace), wb,
+                               _stream(stream)), "tman_mpgemm")

@@ -1,0 +1,106 @@
+// C ABI of libtman: argument validation, size queries and dispatch to the kernel launchers.
+// Everything here runs on the host and validates before anything is enqueued.
+#include "tman_internal.h"
+
+using namespace tman;
+
+extern "C" {
+
+size_t tman_packed_bytes(const tman_shape_t* shape) {
+    if (check_shape(shape) != TMAN_OK) return 0;
+    return make_layout(shape).total_bytes;
+}
+
+size_t tman_lut_bytes(int32_t N, int32_t K, int32_t group) {
+    if (N < 1 || N > TMAN_MAX_DECODE_TOKENS || K < 1) return 0;
+    if (group != 32 && group != 64 && group != 128) return 0;
+    if (K % group != 0) return 0;
+    size_t nkt = (size_t)(K + kKTile - 1) / kKTile;
+    size_t np = (size_t)padded_tokens(N);
+    return nkt * kTableBytesPerKTile * np + nkt * (kKTile / group) * np * sizeof(float);
+}
+
+size_t tman_mpgemv_workspace_bytes(const tman_shape_t* shape, int32_t N) {
+    if (check_shape(shape) != TMAN_OK || N < 1 || N > TMAN_MAX_DECODE_TOKENS) return 0;
+    GemvPlan p = plan_gemv(make_layout(shape), N);
+    return p.ticket_bytes + p.partial_bytes;
+}
+
+size_t tman_mpgemm_workspace_bytes(const tman_shape_t* shape, int32_t N) {
+    (void)shape;
+    (void)N;
+    return 0;
+}
+
+int tman_pack_weights(const tman_shape_t* shape, const uint8_t* codes, const void* scales, const void* zeros,
+                      void* packed, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != TMAN_OK) return rc;
+    if (!codes || !scales || !packed) return TMAN_ERR_NULL;
+    bool hz = shape->flags & TMAN_FLAG_HAS_ZERO;
+    if (hz && !zeros) return TMAN_ERR_NULL;
+    if (!hz && zeros) return TMAN_ERR_SHAPE;
+    if (!aligned16(packed)) return TMAN_ERR_ALIGN;
+    return launch_pack(make_layout(shape), codes, scales, zeros, packed, (hipStream_t)stream);
+}
+
+int tman_unpack_weights(const tman_shape_t* shape, const void* packed, uint8_t* codes, void* scales, void* zeros,
+                        void* stream) {
+    int rc = check_shape(shape);
+    if (rc != TMAN_OK) return rc;
+    if (!packed || !codes) return TMAN_ERR_NULL;
+    if (!aligned16(packed)) return TMAN_ERR_ALIGN;
+    if (zeros && !(shape->flags & TMAN_FLAG_HAS_ZERO)) return TMAN_ERR_SHAPE;
+    return launch_unpack(make_layout(shape), packed, codes, scales, zeros, (hipStream_t)stream);
+}
+
+int tman_build_lut(const void* x, int32_t N, int32_t K, int32_t group, void* lut, void* stream) {
+    if (!x || !lut) return TMAN_ERR_NULL;
+    if (group != 32 && group != 64 && group != 128) return TMAN_ERR_GROUP;
+    if (N < 1 || N > TMAN_MAX_DECODE_TOKENS || K < 1 || K % group != 0) return TMAN_ERR_SHAPE;
+    if (!aligned16(lut)) return TMAN_ERR_ALIGN;
+    return launch_build_lut(x, N, K, group, lut, (hipStream_t)stream);
+}
+
+int tman_mpgemv(const tman_shape_t* shape, const void* packed, const void* lut, int32_t N, void* y, void* workspace,
+                size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != TMAN_OK) return rc;
+    if (!packed || !lut || !y) return TMAN_ERR_NULL;
+    if (N < 1 || N > TMAN_MAX_DECODE_TOKENS) return TMAN_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(lut)) return TMAN_ERR_ALIGN;
+    size_t need = tman_mpgemv_workspace_bytes(shape, N);
+    if (need && (!workspace || workspace_bytes < need)) return TMAN_ERR_WORKSPACE;
+    if (workspace && !aligned16(workspace)) return TMAN_ERR_ALIGN;
+    return launch_mpgemv(make_layout(shape), packed, lut, N, y, workspace, (hipStream_t)stream);
+}
+
+int tman_mpgemm(const tman_shape_t* shape, const void* packed, const void* x, int32_t N, void* y, void* workspace,
+                size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != TMAN_OK) return rc;
+    if (!packed || !x || !y) return TMAN_ERR_NULL;
+    if (N < 1) return TMAN_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(x)) return TMAN_ERR_ALIGN;
+    size_t need = tman_mpgemm_workspace_bytes(shape, N);
+    if (need && (!workspace || workspace_bytes < need)) return TMAN_ERR_WORKSPACE;
+    return launch_mpgemm(make_layout(shape), packed, x, N, y, workspace, (hipStream_t)stream);
+}
+
+const char* tman_status_string(int status) {
+    switch (status) {
+        case TMAN_OK: return "ok";
+        case TMAN_ERR_NULL: return "null pointer";
+        case TMAN_ERR_BITS: return "bits must be 1, 2 or 4";
+        case TMAN_ERR_GROUP: return "group must be 32, 64 or 128";
+        case TMAN_ERR_SHAPE: return "invalid shape, token count or flags";
+        case TMAN_ERR_WORKSPACE: return "workspace missing or too small";
+        case TMAN_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case TMAN_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int32_t tman_layout_version(void) { return kLayoutVersion; }
+
+}  // extern "C"

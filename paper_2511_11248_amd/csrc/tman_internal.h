@@ -1,0 +1,86 @@
+// Internal definitions shared by the HIP translation units of libtman (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tman.h"
+
+namespace tman {
+
+// Packed-weight geometry.  A tile block is 32 rows x 256 columns; each of its 64 lanes
+// (row % 32 + 32 * half) owns 128 weights of one row.
+constexpr int kHeaderBytes = 128;
+constexpr int kRows = 32;
+constexpr int kKTile = 256;
+constexpr int kHalf = 128;
+constexpr int kLayoutVersion = 1;
+constexpr int kLutGroup = 4;                       // activations per table (16-entry tables)
+constexpr int kTablesPerKTile = kKTile / kLutGroup;  // 64
+constexpr int kTableBytesPerKTile = kTablesPerKTile * 16 * 2;  // fp16 entries, one token
+
+struct Layout {
+    int M, K, bits, group, has_zero;
+    int n_row_blocks, n_ktiles;
+    int groups_per_half;  // 128 / group
+    int meta_entry;       // bytes per (scale[, zero]) entry
+    int meta_per_lane;    // groups_per_half * meta_entry
+    int tile_bytes;       // bits * 1024 + 64 * meta_per_lane
+    size_t total_bytes;
+};
+
+inline int check_shape(const tman_shape_t* s) {
+    if (!s) return TMAN_ERR_NULL;
+    if (s->bits != 1 && s->bits != 2 && s->bits != 4) return TMAN_ERR_BITS;
+    if (s->group != 32 && s->group != 64 && s->group != 128) return TMAN_ERR_GROUP;
+    if (s->M < 1 || s->K < 1 || s->K % s->group != 0) return TMAN_ERR_SHAPE;
+    if (s->flags & ~TMAN_FLAG_HAS_ZERO) return TMAN_ERR_SHAPE;
+    if (!(s->flags & TMAN_FLAG_HAS_ZERO) && s->bits != 1) return TMAN_ERR_SHAPE;  // sign form is 1-bit only
+    return TMAN_OK;
+}
+
+inline Layout make_layout(const tman_shape_t* s) {
+    Layout L;
+    L.M = s->M;
+    L.K = s->K;
+    L.bits = s->bits;
+    L.group = s->group;
+    L.has_zero = (s->flags & TMAN_FLAG_HAS_ZERO) ? 1 : 0;
+    L.n_row_blocks = (s->M + kRows - 1) / kRows;
+    L.n_ktiles = (s->K + kKTile - 1) / kKTile;
+    L.groups_per_half = kHalf / s->group;
+    L.meta_entry = L.has_zero ? 4 : 2;
+    L.meta_per_lane = L.groups_per_half * L.meta_entry;
+    L.tile_bytes = s->bits * 1024 + 64 * L.meta_per_lane;
+    L.total_bytes = (size_t)kHeaderBytes + (size_t)L.n_row_blocks * L.n_ktiles * L.tile_bytes;
+    return L;
+}
+
+// tokens are padded to 1, 2, 4 or 8 inside the lookup-table buffer
+inline int padded_tokens(int N) { return N <= 1 ? 1 : N <= 2 ? 2 : N <= 4 ? 4 : 8; }
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? TMAN_OK : TMAN_ERR_LAUNCH; }
+
+// decode split-K plan (host): how the K tiles of one GEMV are sliced over workgroups
+struct GemvPlan {
+    int np;           // padded tokens
+    int ktiles_per_slice;
+    int n_slices;
+    int n_row_groups;  // workgroups along M (4 row blocks each)
+    size_t lds_bytes;
+    size_t ticket_bytes;
+    size_t partial_bytes;
+};
+GemvPlan plan_gemv(const Layout& L, int N);
+
+// launchers (each returns a tman_status)
+int launch_pack(const Layout& L, const uint8_t* codes, const void* scales, const void* zeros, void* packed,
+                hipStream_t st);
+int launch_unpack(const Layout& L, const void* packed, uint8_t* codes, void* scales, void* zeros, hipStream_t st);
+int launch_build_lut(const void* x, int N, int K, int group, void* lut, hipStream_t st);
+int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
+                  hipStream_t st);
+int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);
+
+}  // namespace tman

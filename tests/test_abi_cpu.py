@@ -1,0 +1,127 @@
+"""Host-side checks of the C-ABI library: it loads, exports every declared symbol, answers the size
+queries consistently with the documented layout, and rejects bad arguments before launching
+anything (so none of this needs a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_2511_11248_amd as tman
+from paper_2511_11248_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(tman.library_path()):
+        from paper_2511_11248_amd import build
+
+        build.build(verbose=False)
+    return api._load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    with open(os.path.join(ROOT, "include", "tman.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    names = set(re.findall(r"\b(tman_[a-z_]+)\s*\(", text))
+    assert {"tman_pack_weights", "tman_build_lut", "tman_mpgemv", "tman_mpgemm"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in tman.h but not exported"
+
+
+def test_binding_has_same_names():
+    for n in ("tman_pack_weights", "tman_unpack_weights", "tman_build_lut", "tman_mpgemv", "tman_mpgemm",
+              "tman_packed_bytes", "tman_lut_bytes", "tman_mpgemv_workspace_bytes", "tman_mpgemm_workspace_bytes",
+              "tman_status_string", "tman_layout_version"):
+        assert callable(getattr(tman, n))
+
+
+@pytest.mark.parametrize("M,K,bits,group,hz", [
+    (256, 512, 4, 64, True), (12288, 4096, 2, 64, True), (4096, 11008, 4, 128, True), (3072, 8192, 1, 64, False),
+    (33, 96, 2, 32, True), (1, 32, 4, 32, True), (100, 384, 1, 128, True),
+])
+def test_packed_bytes_match_layout(lib, M, K, bits, group, hz):
+    L = oracle.PackedLayout(M, K, bits, group, hz)
+    assert tman.tman_packed_bytes(tman.Shape(M, K, bits, group, hz)) == L.total_bytes
+
+
+def test_packed_bytes_are_the_algorithmic_bytes_on_aligned_shapes(lib):
+    # bits/8 + 4/group bytes per weight (2/group without zeros), plus the 128-byte header
+    for M, K, bits, group, hz, per_w in [(12288, 4096, 2, 64, True, 0.3125), (4096, 11008, 4, 128, True, 0.53125),
+                                         (11008, 4096, 4, 64, True, 0.5625), (3072, 8192, 1, 64, False, 0.15625)]:
+        assert tman.tman_packed_bytes(tman.Shape(M, K, bits, group, hz)) == 128 + int(M * K * per_w)
+
+
+def test_lut_bytes(lib):
+    assert tman.tman_lut_bytes(1, 4096, 64) == 4096 // 4 * 16 * 2 + (4096 // 64) * 4
+    assert tman.tman_lut_bytes(3, 512, 64) == (512 // 4 * 16 * 2 + (512 // 64) * 4) * 4  # padded to 4 tokens
+    assert tman.tman_lut_bytes(8, 11008, 128) == (11008 // 4 * 16 * 2 + (11008 // 128) * 4) * 8
+    assert tman.tman_lut_bytes(1, 96, 32) == 2048 + 8 * 4  # K padded to one 256-column tile
+    assert tman.tman_lut_bytes(0, 4096, 64) == 0
+    assert tman.tman_lut_bytes(9, 4096, 64) == 0
+    assert tman.tman_lut_bytes(1, 4096, 48) == 0
+    assert tman.tman_lut_bytes(1, 100, 64) == 0
+
+
+def _shape(M=64, K=256, bits=4, group=64, flags=1):
+    return api._CShape(M, K, bits, group, flags)
+
+
+FAKE = 0x1000  # non-NULL, 16-byte aligned, never dereferenced: validation fails first
+
+
+@pytest.mark.parametrize("shape,status", [
+    (_shape(bits=3), -2), (_shape(bits=0), -2), (_shape(bits=8), -2),
+    (_shape(group=48), -3), (_shape(group=256), -3), (_shape(group=0), -3),
+    (_shape(M=0), -4), (_shape(K=0), -4), (_shape(K=200), -4), (_shape(flags=2), -4),
+    (_shape(bits=2, flags=0), -4),
+])
+def test_bad_shapes_are_rejected_everywhere(lib, shape, status):
+    assert lib.tman_packed_bytes(C.byref(shape)) == 0
+    assert lib.tman_mpgemv_workspace_bytes(C.byref(shape), 1) == 0
+    assert lib.tman_pack_weights(C.byref(shape), FAKE, FAKE, FAKE, FAKE, None) == status
+    assert lib.tman_unpack_weights(C.byref(shape), FAKE, FAKE, None, None, None) == status
+    assert lib.tman_mpgemv(C.byref(shape), FAKE, FAKE, 1, FAKE, FAKE, 1 << 30, None) == status
+    assert lib.tman_mpgemm(C.byref(shape), FAKE, FAKE, 1, FAKE, None, 0, None) == status
+
+
+def test_null_alignment_tokens_workspace(lib):
+    s = _shape()
+    assert lib.tman_pack_weights(None, FAKE, FAKE, FAKE, FAKE, None) == -1
+    assert lib.tman_pack_weights(C.byref(s), None, FAKE, FAKE, FAKE, None) == -1
+    assert lib.tman_pack_weights(C.byref(s), FAKE, None, FAKE, FAKE, None) == -1
+    assert lib.tman_pack_weights(C.byref(s), FAKE, FAKE, None, FAKE, None) == -1  # zeros required with HAS_ZERO
+    assert lib.tman_pack_weights(C.byref(s), FAKE, FAKE, FAKE, None, None) == -1
+    assert lib.tman_pack_weights(C.byref(s), FAKE, FAKE, FAKE, FAKE + 4, None) == -6
+    sign = _shape(bits=1, flags=0)
+    assert lib.tman_pack_weights(C.byref(sign), FAKE, FAKE, FAKE, FAKE, None) == -4  # zeros given, format has none
+    assert lib.tman_build_lut(None, 1, 256, 64, FAKE, None) == -1
+    assert lib.tman_build_lut(FAKE, 1, 256, 64, None, None) == -1
+    assert lib.tman_build_lut(FAKE, 0, 256, 64, FAKE, None) == -4
+    assert lib.tman_build_lut(FAKE, 9, 256, 64, FAKE, None) == -4
+    assert lib.tman_build_lut(FAKE, 1, 250, 64, FAKE, None) == -4
+    assert lib.tman_build_lut(FAKE, 1, 256, 100, FAKE, None) == -3
+    assert lib.tman_build_lut(FAKE, 1, 256, 64, FAKE + 8, None) == -6
+    assert lib.tman_mpgemv(C.byref(s), None, FAKE, 1, FAKE, FAKE, 1 << 30, None) == -1
+    assert lib.tman_mpgemv(C.byref(s), FAKE, FAKE, 0, FAKE, FAKE, 1 << 30, None) == -4
+    assert lib.tman_mpgemv(C.byref(s), FAKE, FAKE, 9, FAKE, FAKE, 1 << 30, None) == -4
+    need = lib.tman_mpgemv_workspace_bytes(C.byref(s), 1)
+    assert need > 0
+    assert lib.tman_mpgemv(C.byref(s), FAKE, FAKE, 1, FAKE, None, 0, None) == -5
+    assert lib.tman_mpgemv(C.byref(s), FAKE, FAKE, 1, FAKE, FAKE, need - 1, None) == -5
+    assert lib.tman_mpgemv(C.byref(s), FAKE + 2, FAKE, 1, FAKE, FAKE, need, None) == -6
+    assert lib.tman_mpgemm(C.byref(s), FAKE, None, 4, FAKE, None, 0, None) == -1
+    assert lib.tman_mpgemm(C.byref(s), FAKE, FAKE, 0, FAKE, None, 0, None) == -4
+    assert lib.tman_mpgemm(C.byref(s), FAKE, FAKE + 6, 4, FAKE, None, 0, None) == -6
+
+
+def test_status_strings(lib):
+    seen = {tman.tman_status_string(c) for c in range(0, -8, -1)}
+    assert len(seen) == 8 and "unknown status" not in seen
+    assert tman.tman_status_string(-99) == "unknown status"
+    with pytest.raises(tman.TmanError) as e:
+        api._check(-3, "here")
+    assert "group" in str(e.value)

@@ -1,0 +1,72 @@
+"""tman_mpgemm (prefill, table dequantization + MFMA) against the fp64 definition oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2511_11248_amd as tman
+import synth
+from gpu_helpers import TOL, mpgemm, pack, rand_case, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(shape, q, s, z, x):
+    y = mpgemm(shape, pack(shape, q, s, z), x)
+    Y = oracle.matmul(q, s, z, x, shape.bits, shape.group)
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    err = oracle.row_relative_error(y, Y)
+    assert err.max() <= TOL, f"row-normalised error {err.max():.3e} > {TOL}"
+
+
+SMALL = [
+    # M, K, bits, group, has_zero, N
+    (256, 512, 4, 64, True, 128),
+    (256, 512, 4, 64, True, 1),
+    (70, 96, 4, 32, True, 37),       # ragged everywhere, K < one tile
+    (130, 2816, 2, 64, True, 130),   # N spills into a second token tile
+    (96, 1024, 4, 128, True, 256),
+    (64, 768, 1, 64, False, 64),
+    (64, 512, 1, 128, True, 33),
+    (64, 256, 2, 32, True, 200),
+    (1, 32, 4, 32, True, 1),
+    (300, 1280, 4, 64, True, 260),
+]
+
+
+@pytest.mark.parametrize("M,K,bits,group,hz,N", SMALL)
+def test_small_shapes(oracle_lib, M, K, bits, group, hz, N):
+    q, s, z, x = rand_case(3000 + M + K + bits + N, M, K, N, bits, group, hz)
+    _check(tman.Shape(M, K, bits, group, hz), q, s, z, x)
+
+
+def test_identity_activations_return_dequantized_weights(oracle_lib):
+    """X = I (K tokens): Y is dequant(W)^T, each entry within one fp16 rounding of (q - z) * s."""
+    M, K, bits, group = 96, 256, 4, 64
+    q, s, z, _ = rand_case(81, M, K, 1, bits, group)
+    shape = tman.Shape(M, K, bits, group)
+    y = mpgemm(shape, pack(shape, q, s, z), np.eye(K, dtype=np.float16)).astype(np.float64)
+    Wd = (q.astype(np.float64) - np.repeat(z.astype(np.float64), group, axis=1)) * np.repeat(s.astype(np.float64), group, axis=1)
+    assert np.all(np.abs(y - Wd.T) <= 2.0 ** -11 * np.abs(Wd.T) + 1e-12)
+    # and it is exactly the level-2 table entry the oracle defines
+    for m, k in ((0, 0), (5, 63), (95, 255), (40, 130)):
+        D = oracle.dequant_table(int(s[m, k // group].view(np.uint16)), int(z[m, k // group].view(np.uint16)), bits)
+        assert y[k, m] == float(D[q[m, k]])
+
+
+@pytest.mark.parametrize("N", [256, 1024, 2048])
+def test_full_size_prefill_sampled_tokens(oracle_lib, N):
+    """11008 x 4096 uint4 g64 at the benchmarked sizes; the oracle recomputes 24 whole tokens (all 11008
+    outputs each), including the first and last of the batch and of every 128-token tile boundary."""
+    w = synth.WORKLOADS["prefill_w4g64"]
+    spec = w.layers[0]
+    q, s, z = synth.layer_tensors(w, 0, 0)
+    x = synth.activation(w, 0, 0, N)
+    shape = tman.Shape(spec.M, spec.K, w.bits, w.group, True)
+    y = mpgemm(shape, pack(shape, q, s, z), x)
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    rng = np.random.default_rng(N)
+    rows = sorted(set([0, 1, 127, 128, N // 2, N - 129, N - 128, N - 1]) | set(rng.integers(0, N, 16).tolist()))
+    Y = oracle.matmul(q, s, z, x[rows], w.bits, w.group)
+    err = oracle.row_relative_error(y[rows], Y)
+    assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
