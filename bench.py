@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the T-MAN hot path on one MI355X.
+
+Headline (the benchmark spec metric, configs[1]): decode mpGEMV weight GB/s on the 7B-style layer set,
+uint2 weights, group 64, N = 1.  One step = one pass over the layer set: the four lookup-table
+precomputes (one per distinct activation) and the five table-lookup GEMVs (qkv, o, gate, up, down).
+To keep the 256 MB Infinity Cache from serving the weights, the steps rotate over 32 independent
+copies of the layer set (2 GB of packed weights); all inputs are resident in HBM before timing.
+
+The same JSON line also carries the prefill mpGEMM figure (11008 x 4096 uint4 g64, N = 1024) as a
+secondary object, the roofline fraction of the dominant kernel (HIP events around every launch of it
+inside the timed region) and the fp64 CPU oracle timed on the host cores over a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="7b_w2g64")
+    ap.add_argument("--instances", type=int, default=0, help="copies of the layer set to rotate over (0 = workload default)")
+    ap.add_argument("--prefill-tokens", type=int, default=1024)
+    ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2511_11248_amd as tman
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    w = synth.WORKLOADS[args.workload]
+    n_inst = args.instances or w.instances
+    N = 1
+    # ------------------------------------------------------------------ inputs, resident in HBM
+    shapes = [tman.Shape(l.M, l.K, w.bits, w.group, w.has_zero) for l in w.layers]
+    acts = []  # distinct activation tags in order of first use
+    for l in w.layers:
+        if l.act not in acts:
+            acts.append(l.act)
+    act_of_layer = [acts.index(l.act) for l in w.layers]
+    act_layer0 = [next(i for i, l in enumerate(w.layers) if l.act == a) for a in acts]
+
+    blobs, xs, luts, ys, wss = [], [], [], [], []
+    weight_bytes_per_step = sum(tman.tman_packed_bytes(s) - 128 for s in shapes)
+    for inst in range(n_inst):
+        bl = []
+        for li, s in enumerate(shapes):
+            q, sc, z = synth.layer_tensors(w, inst, li, device=dev)
+            blob = torch.empty(tman.tman_packed_bytes(s), dtype=torch.uint8, device=dev)
+            tman.tman_pack_weights(s, q, sc, z, blob)
+            bl.append(blob)
+            del q
+        blobs.append(bl)
+        xs.append([torch.from_numpy(synth.activation(w, inst, li0, N)).to(dev) for li0 in act_layer0])
+    torch.cuda.synchronize()
+    for ai, li0 in enumerate(act_layer0):
+        K = w.layers[li0].K
+        luts.append(torch.empty(tman.tman_lut_bytes(N, K, w.group), dtype=torch.uint8, device=dev))
+    for s in shapes:
+        ys.append(torch.empty((N, s.M), dtype=torch.float16, device=dev))
+        wss.append(torch.zeros(tman.tman_mpgemv_workspace_bytes(s, N), dtype=torch.uint8, device=dev))
+
+    events = []
+
+    def step(i, record):
+        inst = i % n_inst
+        for ai, li0 in enumerate(act_layer0):
+            tman.tman_build_lut(xs[inst][ai], N, w.layers[li0].K, w.group, luts[ai])
+        for li, s in enumerate(shapes):
+            if record:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            tman.tman_mpgemv(s, blobs[inst][li], luts[act_of_layer[li]], N, ys[li], wss[li])
+            if record:
+                e1.record()
+                events.append((li, e0, e1))
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec_per_step = (t1 - t0) / args.steps
+    value = weight_bytes_per_step / sec_per_step / 1e9
+
+    # dominant kernel: the table-lookup GEMV; average launch duration from the events of the timed region
+    gemv_ms = sum(e0.elapsed_time(e1) for _, e0, e1 in events)
+    n_launch = len(events)
+    avg_launch_s = gemv_ms / 1e3 / n_launch
+    bytes_per_launch = weight_bytes_per_step / len(shapes)
+    achieved = bytes_per_launch / avg_launch_s / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "mpgemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "launches": n_launch, "avg_launch_us": round(avg_launch_s * 1e6, 3),
+        "algorithmic_bytes_per_launch": int(bytes_per_launch),
+    }
+
+    out = {
+        "metric": "decode mpGEMV weight GB/s", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec_per_step * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: 7B-style layer set (qkv 12288x4096, o 4096x4096, gate/up 11008x4096, "
+                               f"down 4096x11008), uint{w.bits} g{w.group}, N=1 decode, {n_inst} rotating copies",
+                   "weight_bytes_per_step": int(weight_bytes_per_step), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+        "roofline": roofline,
+    }
+
+    # ------------------------------------------------------------------ prefill (secondary figure)
+    if not args.no_prefill:
+        pw = synth.WORKLOADS["prefill_w4g64"]
+        spec = pw.layers[0]
+        ps = tman.Shape(spec.M, spec.K, pw.bits, pw.group, True)
+        q, sc, z = synth.layer_tensors(pw, 0, 0, device=dev)
+        pblob = torch.empty(tman.tman_packed_bytes(ps), dtype=torch.uint8, device=dev)
+        tman.tman_pack_weights(ps, q, sc, z, pblob)
+        del q
+        NP = args.prefill_tokens
+        px = torch.from_numpy(synth.activation(pw, 0, 0, NP)).to(dev)
+        py = torch.empty((NP, spec.M), dtype=torch.float16, device=dev)
+        for _ in range(5):
+            tman.tman_mpgemm(ps, pblob, px, NP, py, None)
+        torch.cuda.synchronize()
+        reps = 20
+        pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in pe:
+            a.record()
+            tman.tman_mpgemm(ps, pblob, px, NP, py, None)
+            b.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in pe)
+        avg_ms = sum(ts) / len(ts)
+        flops = 2.0 * NP * spec.M * spec.K
+        tf = flops / (avg_ms / 1e3) / 1e12
+        out["prefill"] = {
+            "metric": "prefill mpGEMM TFLOPS", "value": round(tf, 1), "unit": "TFLOP/s",
+            "config": {"workload": f"{pw.name}: {spec.M}x{spec.K} uint4 g64, N={NP}"},
+            "ms_per_call": round(avg_ms, 4), "min_ms": round(ts[0], 4),
+            "roofline": {"bound": "mfma", "kernel": "mpgemm_kernel", "achieved": round(tf, 1),
+                         "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
+                         "traffic": None},
+        }
+        del pblob, px, py
+
+    # ------------------------------------------------------------------ CPU oracle on the host cores
+    if not args.no_cpu_baseline:
+        import oracle
+
+        oracle.build()
+        done_bytes, cpu_t, cores, used = 0, 0.0, os.cpu_count(), 1
+        sample = []
+        inst = 0
+        while cpu_t < args.cpu_seconds and inst < n_inst:
+            for li, s in enumerate(shapes):
+                q, sc, z = synth.layer_tensors(w, inst, li, device=dev)
+                qh, sh, zh = q.cpu().numpy(), sc.cpu().numpy(), (z.cpu().numpy() if z is not None else None)
+                xh = synth.activation(w, inst, li, N)
+                c0 = time.perf_counter()
+                _, used = oracle.matmul(qh, sh, zh, xh, w.bits, w.group, return_threads=True)
+                cpu_t += time.perf_counter() - c0
+                done_bytes += tman.tman_packed_bytes(s) - 128
+                sample.append(f"{inst}:{w.layers[li].name}")
+                if cpu_t >= args.cpu_seconds:
+                    break
+            inst += 1
+        out["cpu_baseline"] = {
+            "value": round(done_bytes / cpu_t / 1e9, 3), "unit": "GB/s", "cores": int(used), "kind": "oracle",
+            "sample": f"{len(sample)} GEMVs of the same workload (instances 0..{inst - 1}), {cpu_t:.1f} s of fp64 "
+                      f"dequantize-then-multiply; weight bytes counted as for the GPU",
+        }
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

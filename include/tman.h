@@ -72,8 +72,8 @@ size_t tman_mpgemm_workspace_bytes(const tman_shape_t *shape, int32_t N);
  *   zeros  : fp16  [M][K/group], required iff HAS_ZERO, must be NULL otherwise
  *   packed : tman_packed_bytes(shape) bytes, 16-byte aligned; fully overwritten (padding is zeroed)
  * The result is position independent (may be copied, saved and reloaded) and starts with a 128-byte
- * header recording the shape.  Layout: rows in blocks of 32, columns in tiles of 256; inside a tile
- * block each of 64 lanes (row%32 + 32*half) owns 128 weights of one row, stored as `bits` 16-byte
+ * header recording the shape.  Layout: rows in blocks of 64, columns in tiles of 128; inside a tile
+ * block lane (row % 64) owns the 128 weights of its row, stored as `bits` 16-byte
  * chunks (one 1024-byte coalesced sub-block per chunk index) whose 32-bit words are single bit-planes
  * of 32 consecutive weights (weight t of a 4-bit lookup index in bit t, Sec. 4.1 "Bit repacking"),
  * followed by the lane's group scales/zeros.
@@ -114,6 +114,30 @@ int tman_build_lut(const void *x, int32_t N, int32_t K, int32_t group, void *lut
  */
 int tman_mpgemv(const tman_shape_t *shape, const void *packed, const void *lut, int32_t N, void *y, void *workspace,
                 size_t workspace_bytes, void *stream);
+
+/*
+ * Several decoding GEMVs in one launch (Sec. 5 "Graph optimization": layers fed by one activation
+ * share one table; the layers of a decode step are too short to be launched one by one).  All
+ * GEMVs of a batch have the same bits / group / flags and the same N; each has its own packed
+ * weights, lookup-table buffer (buffers may repeat: Q/K/V, gate/up), output and workspace.
+ *
+ * tman_mpgemv_batch_prepare writes a descriptor table of tman_mpgemv_batch_desc_bytes(count) bytes
+ * into `desc` (device memory, 16-byte aligned).  `shapes`, `packed`, `lut`, `y`, `workspace` and
+ * `workspace_bytes` are HOST arrays of `count` entries (the entries of all but `shapes` and
+ * `workspace_bytes` are device pointers); workspace[i] must hold
+ * tman_mpgemv_workspace_bytes(&shapes[i], N) zero-filled bytes and must not be shared between
+ * GEMVs.  The table stays valid while those device buffers stay where they are, so it is built once
+ * and reused for every decode step.
+ * tman_mpgemv_batch_run launches the batch described by `desc`; `count`, `shapes` and `N` must be the
+ * ones given to prepare.  Results are identical to `count` separate tman_mpgemv calls up to the
+ * order of the fp32 additions across K, and deterministic for a given batch.
+ */
+#define TMAN_MAX_BATCH 256
+size_t tman_mpgemv_batch_desc_bytes(int32_t count);
+int tman_mpgemv_batch_prepare(int32_t count, const tman_shape_t *shapes, const void *const *packed,
+                              const void *const *lut, int32_t N, void *const *y, void *const *workspace,
+                              const size_t *workspace_bytes, void *desc, void *stream);
+int tman_mpgemv_batch_run(int32_t count, const tman_shape_t *shapes, int32_t N, const void *desc, void *stream);
 
 /*
  * Prefill mpGEMM (Sec. 4.1 "Fused LUT-based dequantization", Sec. 4.2): bit-planes are repacked to

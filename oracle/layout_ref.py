@@ -6,12 +6,12 @@ kernel read in contiguous blocks (Sec. 4.1 "Unified Layout", "Unified tiling str
 tile picture is hardware specific.  The layout used here is documented as a pure function
 ``(m, k, i) -> (byte, bit)`` and this file is that function written one bit at a time:
 
-* rows are cut into row blocks of 32, columns into K tiles of 256 weights; tile block ``(rb, kt)``
+* rows are cut into row blocks of 64, columns into K tiles of 128 weights; tile block ``(rb, kt)``
   starts at ``128 + (rb * n_ktiles + kt) * tile_bytes``;
-* inside a tile block, "lane" ``l = (m % 32) + 32 * h`` owns the 128 weights ``k = 256 kt + 128 h + [0,128)``
-  of row ``m``; they are cut into ``bits`` chunks of ``128 / bits`` weights; chunk ``v`` of all 64 lanes
-  forms one 1024-byte sub-block (16 bytes per lane), so a 64-lane wave reads it with one coalesced
-  16-byte load per lane;
+* inside a tile block, "lane" ``l = m % 64`` owns the 128 weights ``k = 128 kt + [0,128)`` of row ``m``;
+  they are cut into ``bits`` chunks of ``128 / bits`` weights; chunk ``v`` of all 64 lanes forms one
+  1024-byte sub-block (16 bytes per lane), so a 64-lane wave reads it with one coalesced 16-byte
+  load per lane;
 * the 16 bytes of a chunk are little-endian 32-bit words; word ``ksub * bits + i`` holds bit-plane ``i``
   (bit ``i`` of the codes, Sec. 2.2 one-bit decomposition) of the 32 weights ``ksub * 32 + [0,32)`` of
   the chunk, weight ``beta`` in bit ``beta``.  Four consecutive bits are therefore one 4-bit table
@@ -27,9 +27,8 @@ from dataclasses import dataclass
 import numpy as np
 
 HEADER_BYTES = 128
-ROWS = 32
-KTILE = 256
-HALF = 128
+ROWS = 64
+KTILE = 128
 MAGIC = b"TMANPK1\x00"
 
 
@@ -55,7 +54,7 @@ class PackedLayout:
 
     @property
     def meta_per_lane(self) -> int:
-        return (HALF // self.group) * self.meta_entry
+        return (KTILE // self.group) * self.meta_entry
 
     @property
     def tile_bytes(self) -> int:
@@ -74,13 +73,12 @@ class PackedLayout:
 
     def code_bit_position(self, m, k, i):
         """(byte offset, bit in byte) of plane ``i`` of weight (m, k); arrays broadcast."""
-        chunk = HALF // self.bits
+        chunk = KTILE // self.bits
         rb, r = m // ROWS, m % ROWS
         kt, kk = k // KTILE, k % KTILE
-        h, kh = kk // HALF, kk % HALF
-        v, kc = kh // chunk, kh % chunk
+        v, kc = kk // chunk, kk % chunk
         ksub, beta = kc // 32, kc % 32
-        lane = r + 32 * h
+        lane = r
         off = (HEADER_BYTES + (rb * self.n_ktiles + kt) * self.tile_bytes + v * 1024 + lane * 16
                + (ksub * self.bits + i) * 4 + beta // 8)
         return off, beta % 8
@@ -90,8 +88,8 @@ class PackedLayout:
         k0 = G * self.group
         rb, r = m // ROWS, m % ROWS
         kt, kk = k0 // KTILE, k0 % KTILE
-        h, gi = kk // HALF, (kk % HALF) // self.group
-        lane = r + 32 * h
+        gi = kk // self.group
+        lane = r
         return (HEADER_BYTES + (rb * self.n_ktiles + kt) * self.tile_bytes + self.bits * 1024
                 + lane * self.meta_per_lane + gi * self.meta_entry)
 
@@ -144,15 +142,15 @@ def lut_layout_decode(buf: np.ndarray, N: int, K: int, group: int):
     """Read the lookup-table buffer written for ``N`` tokens back into T[n][j][p] (fp16) and
     S[n][G] (fp32).
 
-    Documented layout: tokens are padded to NP = 1, 2, 4 or 8 and K to a multiple of 256 (n_ktiles
+    Documented layout: tokens are padded to NP = 1, 2, 4 or 8 and K to a multiple of 128 (n_ktiles
     tiles); fp16 entry (n, j, p) sits at element ``(j * 16 + p) * NP + n`` (table j covers
     activations 4j..4j+3, pattern bit t selects activation 4j+t); the fp32 group sums follow at
-    byte ``n_ktiles * 2048 * NP``, element ``G * NP + n``."""
+    byte ``n_ktiles * 1024 * NP``, element ``G * NP + n``."""
     NP = 1 if N == 1 else 2 if N == 2 else 4 if N <= 4 else 8
     nkt = -(-K // KTILE)
     buf = np.asarray(buf, dtype=np.uint8)
-    t_bytes = nkt * 2048 * NP
-    T = buf[:t_bytes].view(np.float16).reshape(nkt * 64, 16, NP)
+    t_bytes = nkt * 1024 * NP
+    T = buf[:t_bytes].view(np.float16).reshape(nkt * 32, 16, NP)
     T = np.transpose(T, (2, 0, 1))[:N, : K // 4, :]
     n_groups_padded = nkt * (KTILE // group)
     S = buf[t_bytes:t_bytes + n_groups_padded * NP * 4].view(np.float32).reshape(n_groups_padded, NP)

@@ -16,6 +16,9 @@ from .api import (  # noqa: F401
     tman_build_lut,
     tman_mpgemv,
     tman_mpgemm,
+    tman_mpgemv_batch_desc_bytes,
+    tman_mpgemv_batch_prepare,
+    tman_mpgemv_batch_run,
     tman_status_string,
     tman_layout_version,
 )

@@ -72,6 +72,12 @@ def _load():
         L.tman_build_lut.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]
         L.tman_mpgemv.restype = C.c_int
         L.tman_mpgemv.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.tman_mpgemv_batch_desc_bytes.restype = C.c_size_t
+        L.tman_mpgemv_batch_desc_bytes.argtypes = [C.c_int32]
+        L.tman_mpgemv_batch_prepare.restype = C.c_int
+        L.tman_mpgemv_batch_prepare.argtypes = [C.c_int32, sp, vp, vp, C.c_int32, vp, vp, vp, vp, vp]
+        L.tman_mpgemv_batch_run.restype = C.c_int
+        L.tman_mpgemv_batch_run.argtypes = [C.c_int32, sp, C.c_int32, vp, vp]
         L.tman_mpgemm.restype = C.c_int
         L.tman_mpgemm.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
         L.tman_status_string.restype = C.c_char_p
@@ -161,3 +167,29 @@ def tman_mpgemm(shape: Shape, packed, x, N: int, y, workspace=None, stream=None)
     wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
     _check(_load().tman_mpgemm(C.byref(shape.c()), _ptr(packed), _ptr(x), N, _ptr(y), _ptr(workspace), wb,
                                _stream(stream)), "tman_mpgemm")
+
+
+def tman_mpgemv_batch_desc_bytes(count: int) -> int:
+    return int(_load().tman_mpgemv_batch_desc_bytes(count))
+
+
+def _batch_arrays(shapes, packed, lut, y, workspace):
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    vp = C.c_void_p * n
+    return (n, cs, vp(*[_ptr(t) for t in packed]), vp(*[_ptr(t) for t in lut]), vp(*[_ptr(t) for t in y]),
+            vp(*[_ptr(t) for t in workspace]), (C.c_size_t * n)(*[_nbytes(t) for t in workspace]))
+
+
+def tman_mpgemv_batch_prepare(shapes, packed, lut, N: int, y, workspace, desc, stream=None) -> None:
+    """Write the device descriptor table for a batch of GEMVs (lists of equal length; lut entries may
+    repeat).  The table is reusable for every step while the buffers stay in place."""
+    n, cs, pk, lt, yy, ws, wb = _batch_arrays(shapes, packed, lut, y, workspace)
+    _check(_load().tman_mpgemv_batch_prepare(n, cs, pk, lt, N, yy, ws, wb, _ptr(desc), _stream(stream)),
+           "tman_mpgemv_batch_prepare")
+
+
+def tman_mpgemv_batch_run(shapes, N: int, desc, stream=None) -> None:
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    _check(_load().tman_mpgemv_batch_run(n, cs, N, _ptr(desc), _stream(stream)), "tman_mpgemv_batch_run")

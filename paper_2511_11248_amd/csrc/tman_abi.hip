@@ -75,6 +75,61 @@ int tman_mpgemv(const tman_shape_t* shape, const void* packed, const void* lut, 
     return launch_mpgemv(make_layout(shape), packed, lut, N, y, workspace, (hipStream_t)stream);
 }
 
+size_t tman_mpgemv_batch_desc_bytes(int32_t count) {
+    if (count < 1 || count > TMAN_MAX_BATCH) return 0;
+    return (size_t)count * sizeof(GemvDesc);
+}
+
+static int check_batch(int32_t count, const tman_shape_t* shapes, int32_t N) {
+    if (!shapes) return TMAN_ERR_NULL;
+    if (count < 1 || count > TMAN_MAX_BATCH) return TMAN_ERR_SHAPE;
+    if (N < 1 || N > TMAN_MAX_DECODE_TOKENS) return TMAN_ERR_SHAPE;
+    long long total = 0;
+    for (int i = 0; i < count; ++i) {
+        int rc = check_shape(&shapes[i]);
+        if (rc != TMAN_OK) return rc;
+        if (shapes[i].bits != shapes[0].bits || shapes[i].group != shapes[0].group ||
+            shapes[i].flags != shapes[0].flags)
+            return TMAN_ERR_SHAPE;  // one launch runs one weight format
+        total += plan_gemv(make_layout(&shapes[i]), N).n_workgroups;
+    }
+    if (total > 0x7fffffffLL) return TMAN_ERR_SHAPE;
+    return TMAN_OK;
+}
+
+int tman_mpgemv_batch_prepare(int32_t count, const tman_shape_t* shapes, const void* const* packed,
+                              const void* const* lut, int32_t N, void* const* y, void* const* workspace,
+                              const size_t* workspace_bytes, void* desc, void* stream) {
+    int rc = check_batch(count, shapes, N);
+    if (rc != TMAN_OK) return rc;
+    if (!packed || !lut || !y || !workspace || !workspace_bytes || !desc) return TMAN_ERR_NULL;
+    if (!aligned16(desc)) return TMAN_ERR_ALIGN;
+    GemvDesc host[TMAN_MAX_BATCH];
+    int wg_begin = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!packed[i] || !lut[i] || !y[i] || !workspace[i]) return TMAN_ERR_NULL;
+        if (!aligned16(packed[i]) || !aligned16(lut[i]) || !aligned16(workspace[i])) return TMAN_ERR_ALIGN;
+        if (workspace_bytes[i] < tman_mpgemv_workspace_bytes(&shapes[i], N)) return TMAN_ERR_WORKSPACE;
+        for (int j = 0; j < i; ++j)
+            if (workspace[j] == workspace[i]) return TMAN_ERR_WORKSPACE;  // every GEMV needs its own
+        Layout L = make_layout(&shapes[i]);
+        fill_desc(host[i], L, packed[i], lut[i], N, y[i], workspace[i], wg_begin);
+        wg_begin += plan_gemv(L, N).n_workgroups;
+    }
+    return launch_write_descs(host, count, static_cast<GemvDesc*>(desc), (hipStream_t)stream);
+}
+
+int tman_mpgemv_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, const void* desc, void* stream) {
+    int rc = check_batch(count, shapes, N);
+    if (rc != TMAN_OK) return rc;
+    if (!desc) return TMAN_ERR_NULL;
+    if (!aligned16(desc)) return TMAN_ERR_ALIGN;
+    long long total = 0;
+    for (int i = 0; i < count; ++i) total += plan_gemv(make_layout(&shapes[i]), N).n_workgroups;
+    return launch_mpgemv_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO, N,
+                               static_cast<const GemvDesc*>(desc), count, total, (hipStream_t)stream);
+}
+
 int tman_mpgemm(const tman_shape_t* shape, const void* packed, const void* x, int32_t N, void* y, void* workspace,
                 size_t workspace_bytes, void* stream) {
     int rc = check_shape(shape);

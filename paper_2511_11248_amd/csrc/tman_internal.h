@@ -7,23 +7,22 @@
 
 namespace tman {
 
-// Packed-weight geometry.  A tile block is 32 rows x 256 columns; each of its 64 lanes
-// (row % 32 + 32 * half) owns 128 weights of one row.
+// Packed-weight geometry.  A tile block is 64 rows x 128 columns; lane (row % 64) owns the 128
+// weights of its row.
 constexpr int kHeaderBytes = 128;
-constexpr int kRows = 32;
-constexpr int kKTile = 256;
-constexpr int kHalf = 128;
+constexpr int kRows = 64;
+constexpr int kKTile = 128;
 constexpr int kLayoutVersion = 1;
 constexpr int kLutGroup = 4;                       // activations per table (16-entry tables)
-constexpr int kTablesPerKTile = kKTile / kLutGroup;  // 64
+constexpr int kTablesPerKTile = kKTile / kLutGroup;  // 32
 constexpr int kTableBytesPerKTile = kTablesPerKTile * 16 * 2;  // fp16 entries, one token
 
 struct Layout {
     int M, K, bits, group, has_zero;
     int n_row_blocks, n_ktiles;
-    int groups_per_half;  // 128 / group
+    int groups_per_tile;  // 128 / group
     int meta_entry;       // bytes per (scale[, zero]) entry
-    int meta_per_lane;    // groups_per_half * meta_entry
+    int meta_per_lane;    // groups_per_tile * meta_entry
     int tile_bytes;       // bits * 1024 + 64 * meta_per_lane
     size_t total_bytes;
 };
@@ -47,9 +46,9 @@ inline Layout make_layout(const tman_shape_t* s) {
     L.has_zero = (s->flags & TMAN_FLAG_HAS_ZERO) ? 1 : 0;
     L.n_row_blocks = (s->M + kRows - 1) / kRows;
     L.n_ktiles = (s->K + kKTile - 1) / kKTile;
-    L.groups_per_half = kHalf / s->group;
+    L.groups_per_tile = kKTile / s->group;
     L.meta_entry = L.has_zero ? 4 : 2;
-    L.meta_per_lane = L.groups_per_half * L.meta_entry;
+    L.meta_per_lane = L.groups_per_tile * L.meta_entry;
     L.tile_bytes = s->bits * 1024 + 64 * L.meta_per_lane;
     L.total_bytes = (size_t)kHeaderBytes + (size_t)L.n_row_blocks * L.n_ktiles * L.tile_bytes;
     return L;
@@ -62,17 +61,34 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? TMAN_OK : TMAN_ERR_LAUNCH; }
 
-// decode split-K plan (host): how the K tiles of one GEMV are sliced over workgroups
+// Decode scheduling: a workgroup (four waves) owns one row block and one K segment of at most this
+// many tiles; longer K is cut into equal segments that meet through the workspace.
+constexpr int kGemvSegmentTiles = 32;
+
+// One GEMV of a decode launch, as the kernel sees it.
+struct GemvDesc {
+    const uint8_t* tiles;  // first tile block (past the header)
+    const uint8_t* lut_t;  // fp16 tables
+    const uint8_t* lut_s;  // fp32 group sums
+    void* y;               // fp16 [N][M]
+    int32_t* tickets;      // [n_row_blocks], zero between launches
+    float* partial;        // [n_row_blocks][n_seg][NP][64]
+    int M, N, n_row_blocks, n_ktiles;
+    int wg_begin;          // index of this GEMV's first workgroup in the launch
+    int n_seg;             // K segments per row block
+    int seg_tiles;         // tiles per segment (the last may be shorter)
+    int pad;
+};
+
 struct GemvPlan {
-    int np;           // padded tokens
-    int ktiles_per_slice;
-    int n_slices;
-    int n_row_groups;  // workgroups along M (4 row blocks each)
-    size_t lds_bytes;
+    int np;  // padded tokens
+    int n_seg, seg_tiles, n_workgroups;
     size_t ticket_bytes;
     size_t partial_bytes;
 };
 GemvPlan plan_gemv(const Layout& L, int N);
+void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
+               int wg_begin);
 
 // launchers (each returns a tman_status)
 int launch_pack(const Layout& L, const uint8_t* codes, const void* scales, const void* zeros, void* packed,
@@ -81,6 +97,9 @@ int launch_unpack(const Layout& L, const void* packed, uint8_t* codes, void* sca
 int launch_build_lut(const void* x, int N, int K, int group, void* lut, hipStream_t st);
 int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
                   hipStream_t st);
+int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,
+                        long long total_tiles, hipStream_t st);
+int launch_write_descs(const GemvDesc* host, int count, GemvDesc* dev, hipStream_t st);
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);
 
 }  // namespace tman

@@ -7,9 +7,9 @@
 // fp32 sum taken in ascending t.  The fp32 sums S[n][G] of x over each quantization block follow;
 // the GEMV needs them for the zero-point term.
 //
-// Buffer layout (tokens padded to NP = 1, 2, 4 or 8; K padded to a multiple of 256 with zeros):
-//   fp16 element (j * 16 + p) * NP + n          for j < n_ktiles * 64
-//   fp32 element  G * NP + n                    at byte offset n_ktiles * 2048 * NP, G < n_ktiles * 256 / group
+// Buffer layout (tokens padded to NP = 1, 2, 4 or 8; K padded to a multiple of 128 with zeros):
+//   fp16 element (j * 16 + p) * NP + n          for j < n_ktiles * 32
+//   fp32 element  G * NP + n                    at byte offset n_ktiles * 1024 * NP, G < n_ktiles * 128 / group
 // so the slice of one K tile is contiguous and can be copied to LDS as it is.
 #include <hip/hip_fp16.h>
 

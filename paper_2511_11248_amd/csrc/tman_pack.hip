@@ -4,8 +4,8 @@
 // the form decoding needs, and pre-permutes them so both kernels fetch contiguous blocks.  Here one
 // thread owns 32 consecutive weights of one row: it splits their codes into `bits` one-bit planes
 // (Sec. 2.2 one-bit decomposition) and writes one 32-bit word per plane at the position the layout
-// function assigns.  The padded domain (rows up to a multiple of 32, columns up to a multiple of
-// 256) is covered too, so the blob is completely defined.
+// function assigns.  The padded domain (rows up to a multiple of 64, columns up to a multiple of
+// 128) is covered too, so the blob is completely defined.
 #include "tman_internal.h"
 
 namespace tman {
@@ -22,25 +22,21 @@ static PackGeom geom_of(const Layout& L) {
 
 // byte offset (from the blob start) of the 32-bit word holding plane i of weights k32*32 .. +31 of row m
 __device__ __forceinline__ size_t word_offset(const PackGeom& g, int m, int k32, int i) {
-    int rb = m >> 5, r = m & 31;
+    int rb = m / kRows, lane = m % kRows;
     int k = k32 << 5;
-    int kt = k >> 8, kk = k & 255;
-    int h = kk >> 7, kh = kk & 127;
-    int chunk = kHalf / g.bits;  // weights per 16-byte chunk
-    int v = kh / chunk, kc = kh % chunk;
+    int kt = k / kKTile, kk = k % kKTile;
+    int chunk = kKTile / g.bits;  // weights per 16-byte chunk
+    int v = kk / chunk, kc = kk % chunk;
     int ksub = kc >> 5;
-    int lane = r + 32 * h;
     return (size_t)kHeaderBytes + ((size_t)rb * g.n_ktiles + kt) * g.tile_bytes + v * 1024 + lane * 16 +
            (ksub * g.bits + i) * 4;
 }
 
 // byte offset of the scale of (row m, quantization group G); the zero follows at +2
 __device__ __forceinline__ size_t meta_offset(const PackGeom& g, int m, int G) {
-    int rb = m >> 5, r = m & 31;
+    int rb = m / kRows, lane = m % kRows;
     int k0 = G * g.group;
-    int kt = k0 >> 8, kk = k0 & 255;
-    int h = kk >> 7, gi = (kk & 127) / g.group;
-    int lane = r + 32 * h;
+    int kt = k0 / kKTile, gi = (k0 % kKTile) / g.group;
     return (size_t)kHeaderBytes + ((size_t)rb * g.n_ktiles + kt) * g.tile_bytes + g.bits * 1024 +
            lane * g.meta_per_lane + gi * g.meta_entry;
 }

@@ -59,7 +59,7 @@ def test_lut_bytes(lib):
     assert tman.tman_lut_bytes(1, 4096, 64) == 4096 // 4 * 16 * 2 + (4096 // 64) * 4
     assert tman.tman_lut_bytes(3, 512, 64) == (512 // 4 * 16 * 2 + (512 // 64) * 4) * 4  # padded to 4 tokens
     assert tman.tman_lut_bytes(8, 11008, 128) == (11008 // 4 * 16 * 2 + (11008 // 128) * 4) * 8
-    assert tman.tman_lut_bytes(1, 96, 32) == 2048 + 8 * 4  # K padded to one 256-column tile
+    assert tman.tman_lut_bytes(1, 96, 32) == 1024 + 4 * 4  # K padded to one 128-column tile
     assert tman.tman_lut_bytes(0, 4096, 64) == 0
     assert tman.tman_lut_bytes(9, 4096, 64) == 0
     assert tman.tman_lut_bytes(1, 4096, 48) == 0

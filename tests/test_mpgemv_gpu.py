@@ -137,3 +137,75 @@ def test_full_size_layer_sets(oracle_lib, name, N):
         shape = tman.Shape(spec.M, spec.K, w.bits, w.group, w.has_zero)
         print(f"{name} layer {spec.name} {spec.M}x{spec.K} N={N}", flush=True)
         _check(shape, q, s, z, x)
+
+
+def _run_batch(w, instance, N, layer_ids):
+    """One tman_mpgemv_batch launch over the given layers of a workload; returns (outputs, oracle inputs)."""
+    shapes, blobs, luts, ys, wss, ref = [], [], [], [], [], []
+    lut_of_act = {}
+    for li in layer_ids:
+        spec = w.layers[li]
+        q, s, z = synth.layer_tensors(w, instance, li)
+        x = synth.activation(w, instance, li, N)
+        shape = tman.Shape(spec.M, spec.K, w.bits, w.group, w.has_zero)
+        if spec.act not in lut_of_act:
+            xd = to_dev(x)
+            lut = torch.empty(tman.tman_lut_bytes(N, spec.K, w.group), dtype=torch.uint8, device=dev())
+            tman.tman_build_lut(xd, N, spec.K, w.group, lut)
+            lut_of_act[spec.act] = lut
+        shapes.append(shape)
+        blobs.append(pack(shape, q, s, z))
+        luts.append(lut_of_act[spec.act])
+        ys.append(torch.full((N, spec.M), float("nan"), dtype=torch.float16, device=dev()))
+        wss.append(gemv_workspace(shape, N))
+        ref.append((q, s, z, x))
+    desc = torch.empty(tman.tman_mpgemv_batch_desc_bytes(len(shapes)), dtype=torch.uint8, device=dev())
+    tman.tman_mpgemv_batch_prepare(shapes, blobs, luts, N, ys, wss, desc)
+    tman.tman_mpgemv_batch_run(shapes, N, desc)
+    torch.cuda.synchronize()
+    first = [y.cpu().numpy() for y in ys]
+    for y in ys:
+        y.fill_(float("nan"))
+    tman.tman_mpgemv_batch_run(shapes, N, desc)  # the table and the workspaces are reusable
+    torch.cuda.synchronize()
+    second = [y.cpu().numpy() for y in ys]
+    return shapes, first, second, ref, wss
+
+
+@pytest.mark.parametrize("name,N", [("7b_w2g64", 1), ("7b_w4g128", 4), ("3p8b_w1g64", 1)])
+def test_batched_layer_set_full_size(oracle_lib, name, N):
+    """The whole layer set in one launch (the configuration bench.py times): every output against the
+    oracle, two runs bit-identical, tickets left at zero."""
+    w = synth.WORKLOADS[name]
+    shapes, first, second, ref, wss = _run_batch(w, 1, N, list(range(len(w.layers))))
+    for shape, y1, y2, (q, s, z, x), ws in zip(shapes, first, second, ref, wss):
+        assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+        Y = oracle.matmul(q, s, z, x, w.bits, w.group)
+        err = oracle.row_relative_error(y1, Y).max()
+        assert err <= TOL, f"{shape}: {err:.3e}"
+        n_rb = -(-shape.M // 64)
+        assert int(ws[: n_rb * 4].view(torch.int32).abs().sum().item()) == 0
+
+
+def test_batch_of_mixed_small_shapes(oracle_lib):
+    """Ragged M, K below one segment and K over several segments in one launch."""
+    N, bits, group = 2, 4, 64
+    dims = [(70, 192), (64, 4608), (130, 8320), (1, 64), (257, 4096)]
+    shapes, blobs, luts, ys, wss, refs = [], [], [], [], [], []
+    for i, (M, K) in enumerate(dims):
+        q, s, z, x = rand_case(900 + i, M, K, N, bits, group)
+        shape = tman.Shape(M, K, bits, group)
+        lut = torch.empty(tman.tman_lut_bytes(N, K, group), dtype=torch.uint8, device=dev())
+        tman.tman_build_lut(to_dev(x), N, K, group, lut)
+        shapes.append(shape); blobs.append(pack(shape, q, s, z)); luts.append(lut)
+        ys.append(torch.full((N, M), float("nan"), dtype=torch.float16, device=dev()))
+        wss.append(gemv_workspace(shape, N)); refs.append((q, s, z, x))
+    desc = torch.empty(tman.tman_mpgemv_batch_desc_bytes(len(shapes)), dtype=torch.uint8, device=dev())
+    tman.tman_mpgemv_batch_prepare(shapes, blobs, luts, N, ys, wss, desc)
+    tman.tman_mpgemv_batch_run(shapes, N, desc)
+    torch.cuda.synchronize()
+    for shape, y, blob, (q, s, z, x) in zip(shapes, ys, blobs, refs):
+        Y = oracle.matmul(q, s, z, x, bits, group)
+        assert oracle.row_relative_error(y.cpu().numpy(), Y).max() <= TOL
+        single = mpgemv(shape, blob, x)
+        assert np.array_equal(single.view(np.uint16), y.cpu().numpy().view(np.uint16))  # same schedule, same bits
