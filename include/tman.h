@@ -99,6 +99,11 @@ int tman_unpack_weights(const tman_shape_t *shape, const void *packed, uint8_t *
  */
 int tman_build_lut(const void *x, int32_t N, int32_t K, int32_t group, void *lut, void *stream);
 
+/* The same for `count` activations (the distinct inputs of a decode step) in one launch.  `x`, `K` and
+ * `lut` are HOST arrays of `count` entries (x[i], lut[i] device pointers); all share N and group. */
+int tman_build_lut_batch(int32_t count, const void *const *x, int32_t N, const int32_t *K, int32_t group,
+                         void *const *lut, void *stream);
+
 /*
  * Decoding mpGEMV through table lookup (Sec. 2.2, Sec. 4.3):
  *   y[n][m] = sum_G scale[m][G] * ( sum_i 2^i sum_{j in G} T[n][j][idx_i[m][j]] - zero[m][G] * S[n][G] )

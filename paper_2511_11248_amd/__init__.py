@@ -14,11 +14,14 @@ from .api import (  # noqa: F401
     tman_pack_weights,
     tman_unpack_weights,
     tman_build_lut,
+    tman_build_lut_batch,
     tman_mpgemv,
     tman_mpgemm,
     tman_mpgemv_batch_desc_bytes,
     tman_mpgemv_batch_prepare,
     tman_mpgemv_batch_run,
+    bound_build_lut_batch,
+    bound_mpgemv_batch_run,
     tman_status_string,
     tman_layout_version,
 )

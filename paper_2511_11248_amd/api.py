@@ -70,6 +70,8 @@ def _load():
         L.tman_unpack_weights.argtypes = [sp, vp, vp, vp, vp, vp]
         L.tman_build_lut.restype = C.c_int
         L.tman_build_lut.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]
+        L.tman_build_lut_batch.restype = C.c_int
+        L.tman_build_lut_batch.argtypes = [C.c_int32, vp, C.c_int32, vp, C.c_int32, vp, vp]
         L.tman_mpgemv.restype = C.c_int
         L.tman_mpgemv.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
         L.tman_mpgemv_batch_desc_bytes.restype = C.c_size_t
@@ -193,3 +195,36 @@ def tman_mpgemv_batch_run(shapes, N: int, desc, stream=None) -> None:
     n = len(shapes)
     cs = (_CShape * n)(*[s.c() for s in shapes])
     _check(_load().tman_mpgemv_batch_run(n, cs, N, _ptr(desc), _stream(stream)), "tman_mpgemv_batch_run")
+
+
+def tman_build_lut_batch(xs, N: int, Ks, group: int, luts, stream=None) -> None:
+    """Lookup tables for several activations (lists of equal length) in one launch."""
+    n = len(xs)
+    vp = C.c_void_p * n
+    _check(_load().tman_build_lut_batch(n, vp(*[_ptr(t) for t in xs]), N, (C.c_int32 * n)(*Ks), group,
+                                        vp(*[_ptr(t) for t in luts]), _stream(stream)), "tman_build_lut_batch")
+
+
+# Calls that run every decode step with the same arguments can be marshalled once: the returned
+# callables only hand the prebuilt ctypes arguments to the C entry point.
+def bound_build_lut_batch(xs, N: int, Ks, group: int, luts):
+    n = len(xs)
+    vp = C.c_void_p * n
+    fn, args = _load().tman_build_lut_batch, (n, vp(*[_ptr(t) for t in xs]), N, (C.c_int32 * n)(*Ks), group,
+                                               vp(*[_ptr(t) for t in luts]))
+
+    def call(stream_handle):
+        _check(fn(*args, stream_handle), "tman_build_lut_batch")
+
+    return call
+
+
+def bound_mpgemv_batch_run(shapes, N: int, desc):
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    fn, args = _load().tman_mpgemv_batch_run, (n, cs, N, _ptr(desc))
+
+    def call(stream_handle):
+        _check(fn(*args, stream_handle), "tman_mpgemv_batch_run")
+
+    return call

@@ -62,6 +62,19 @@ int tman_build_lut(const void* x, int32_t N, int32_t K, int32_t group, void* lut
     return launch_build_lut(x, N, K, group, lut, (hipStream_t)stream);
 }
 
+int tman_build_lut_batch(int32_t count, const void* const* x, int32_t N, const int32_t* K, int32_t group,
+                         void* const* lut, void* stream) {
+    if (!x || !K || !lut) return TMAN_ERR_NULL;
+    if (group != 32 && group != 64 && group != 128) return TMAN_ERR_GROUP;
+    if (count < 1 || count > TMAN_MAX_BATCH || N < 1 || N > TMAN_MAX_DECODE_TOKENS) return TMAN_ERR_SHAPE;
+    for (int i = 0; i < count; ++i) {
+        if (!x[i] || !lut[i]) return TMAN_ERR_NULL;
+        if (K[i] < 1 || K[i] % group != 0) return TMAN_ERR_SHAPE;
+        if (!aligned16(lut[i])) return TMAN_ERR_ALIGN;
+    }
+    return launch_build_lut_batch(count, x, N, K, group, lut, (hipStream_t)stream);
+}
+
 int tman_mpgemv(const tman_shape_t* shape, const void* packed, const void* lut, int32_t N, void* y, void* workspace,
                 size_t workspace_bytes, void* stream) {
     int rc = check_shape(shape);

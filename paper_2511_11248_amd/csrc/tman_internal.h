@@ -95,6 +95,8 @@ int launch_pack(const Layout& L, const uint8_t* codes, const void* scales, const
                 hipStream_t st);
 int launch_unpack(const Layout& L, const void* packed, uint8_t* codes, void* scales, void* zeros, hipStream_t st);
 int launch_build_lut(const void* x, int N, int K, int group, void* lut, hipStream_t st);
+int launch_build_lut_batch(int count, const void* const* x, int N, const int* K, int group, void* const* lut,
+                           hipStream_t st);
 int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
                   hipStream_t st);
 int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,

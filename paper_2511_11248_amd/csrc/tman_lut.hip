@@ -11,61 +11,103 @@
 //   fp16 element (j * 16 + p) * NP + n          for j < n_ktiles * 32
 //   fp32 element  G * NP + n                    at byte offset n_ktiles * 1024 * NP, G < n_ktiles * 128 / group
 // so the slice of one K tile is contiguous and can be copied to LDS as it is.
+//
+// One launch serves up to 16 activations (the distinct inputs of a decode step): every workgroup
+// finds its activation by its block index, the first blocks of an activation build tables (one
+// thread per table and token), the rest build the group sums (one thread per group and token).
 #include <hip/hip_fp16.h>
 
 #include "tman_internal.h"
 
 namespace tman {
 
-__global__ void __launch_bounds__(256) build_tables_kernel(const _Float16* __restrict__ x, int N, int K, int NP,
-                                                           int n_tables, _Float16* __restrict__ T) {
-    int tid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid >= n_tables * NP) return;
-    int j = tid / NP, n = tid % NP;
-    float a[4] = {0.f, 0.f, 0.f, 0.f};
-    if (n < N) {
-        for (int t = 0; t < 4; ++t) {
-            int k = 4 * j + t;
-            if (k < K) a[t] = (float)x[(size_t)n * K + k];
+struct LutJob {
+    const _Float16* x;
+    _Float16* T;
+    float* S;
+    int K, n_tables, n_groups;
+    int table_blocks;  // blocks that build tables; the group-sum blocks follow
+    int block_begin;   // first block of this activation in the launch
+};
+struct LutJobs {
+    LutJob job[16];
+    int count, N, NP, group;
+};
+
+__global__ void __launch_bounds__(256) build_lut_kernel(LutJobs a) {
+    int ji = 0;
+#pragma unroll 1
+    for (int i = 1; i < a.count; ++i)
+        if ((int)blockIdx.x >= a.job[i].block_begin) ji = i;
+    const LutJob& jb = a.job[ji];
+    const int block = (int)blockIdx.x - jb.block_begin;
+    const int N = a.N, NP = a.NP, K = jb.K;
+    if (block < jb.table_blocks) {
+        const int tid = block * 256 + threadIdx.x;
+        if (tid >= jb.n_tables * NP) return;
+        const int j = tid / NP, n = tid % NP;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (n < N) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int k = 4 * j + t;
+                if (k < K) v[t] = (float)jb.x[(size_t)n * K + k];
+            }
         }
-    }
-    _Float16* dst = T + ((size_t)j * 16) * NP + n;
+        _Float16* dst = jb.T + ((size_t)j * 16) * NP + n;
 #pragma unroll
-    for (int p = 0; p < 16; ++p) {
+        for (int p = 0; p < 16; ++p) {
+            float s = 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if ((p >> t) & 1) s += v[t];
+            dst[(size_t)p * NP] = (_Float16)s;  // round to nearest even
+        }
+    } else {
+        const int tid = (block - jb.table_blocks) * 256 + threadIdx.x;
+        if (tid >= jb.n_groups * NP) return;
+        const int G = tid / NP, n = tid % NP;
         float s = 0.f;
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-            if ((p >> t) & 1) s += a[t];
-        dst[(size_t)p * NP] = (_Float16)s;  // round to nearest even
+        if (n < N) {
+            const int k0 = G * a.group;
+            for (int t = 0; t < a.group; ++t)
+                if (k0 + t < K) s += (float)jb.x[(size_t)n * K + k0 + t];
+        }
+        jb.S[(size_t)G * NP + n] = s;
     }
 }
 
-__global__ void __launch_bounds__(256) group_sums_kernel(const _Float16* __restrict__ x, int N, int K, int NP,
-                                                         int group, int n_groups, float* __restrict__ S) {
-    int tid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (tid >= n_groups * NP) return;
-    int G = tid / NP, n = tid % NP;
-    float s = 0.f;
-    if (n < N) {
-        int k0 = G * group;
-        for (int t = 0; t < group; ++t)
-            if (k0 + t < K) s += (float)x[(size_t)n * K + k0 + t];
+int launch_build_lut_batch(int count, const void* const* x, int N, const int* K, int group, void* const* lut,
+                           hipStream_t st) {
+    const int NP = padded_tokens(N);
+    for (int i0 = 0; i0 < count; i0 += 16) {
+        LutJobs a;
+        a.count = count - i0 < 16 ? count - i0 : 16;
+        a.N = N;
+        a.NP = NP;
+        a.group = group;
+        int blocks = 0;
+        for (int i = 0; i < 16; ++i) {
+            const int src = i0 + (i < a.count ? i : 0);
+            const int nkt = (K[src] + kKTile - 1) / kKTile;
+            LutJob& jb = a.job[i];
+            jb.x = static_cast<const _Float16*>(x[src]);
+            jb.T = static_cast<_Float16*>(lut[src]);
+            jb.S = reinterpret_cast<float*>(static_cast<uint8_t*>(lut[src]) + (size_t)nkt * kTableBytesPerKTile * NP);
+            jb.K = K[src];
+            jb.n_tables = nkt * kTablesPerKTile;
+            jb.n_groups = nkt * (kKTile / group);
+            jb.table_blocks = (jb.n_tables * NP + 255) / 256;
+            jb.block_begin = blocks;
+            if (i < a.count) blocks += jb.table_blocks + (jb.n_groups * NP + 255) / 256;
+        }
+        hipLaunchKernelGGL(build_lut_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
     }
-    S[(size_t)G * NP + n] = s;
+    return launch_status();
 }
 
 int launch_build_lut(const void* x, int N, int K, int group, void* lut, hipStream_t st) {
-    int NP = padded_tokens(N);
-    int nkt = (K + kKTile - 1) / kKTile;
-    int n_tables = nkt * kTablesPerKTile;
-    int n_groups = nkt * (kKTile / group);
-    _Float16* T = static_cast<_Float16*>(lut);
-    float* S = reinterpret_cast<float*>(static_cast<uint8_t*>(lut) + (size_t)nkt * kTableBytesPerKTile * NP);
-    hipLaunchKernelGGL(build_tables_kernel, dim3((n_tables * NP + 255) / 256), dim3(256), 0, st,
-                       static_cast<const _Float16*>(x), N, K, NP, n_tables, T);
-    hipLaunchKernelGGL(group_sums_kernel, dim3((n_groups * NP + 255) / 256), dim3(256), 0, st,
-                       static_cast<const _Float16*>(x), N, K, NP, group, n_groups, S);
-    return launch_status();
+    return launch_build_lut_batch(1, &x, N, &K, group, &lut, st);
 }
 
 }  // namespace tman

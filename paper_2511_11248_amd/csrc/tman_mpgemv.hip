@@ -84,9 +84,9 @@ struct GemvCfg {
     static constexpr int TB = B * 1024 + 64 * MPL;
     static constexpr int T_BYTES = kTableBytesPerKTile * NP;
     static constexpr int S_FLOATS = GPT * NP;
-    static constexpr int SLOT = T_BYTES + 128;  // table slice + group sums, per wave
+    static constexpr int SLOT = T_BYTES + 256;  // table slice + group sums, per wave (multiple of 256)
     // tile blocks in flight per wave, sized by registers: a stage is 4B + 4NP + <=5 VGPRs
-    static constexpr int D = (NP >= 8) ? 1 : (NP == 4 ? 2 : (B == 4 ? 3 : 4));
+    static constexpr int D = (NP >= 8) ? 1 : (NP == 4 ? 2 : (B == 4 ? 2 : (B == 2 ? 3 : 4)));
 };
 
 template <int B, int NP, int MPL>
@@ -120,98 +120,191 @@ __device__ __forceinline__ float half_bits_to_float(uint32_t bits16) {
     return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
 }
 
+// values every lane agrees on, made visibly scalar for the compiler
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ T* uniform(T* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<T*>(((uint64_t)hi << 32) | lo);
+}
+
+// explicit address spaces: descriptor pointers come out of memory as generic pointers, which would
+// turn every access into a flat instruction
+template <typename T>
+using global_ptr = const T __attribute__((address_space(1)))*;
+template <typename T>
+using lds_ptr = T __attribute__((address_space(3)))*;
+
+// wave-uniform base pointer + 32-bit per-lane byte offset: the form that needs no per-lane
+// 64-bit address arithmetic
+template <typename T>
+__device__ __forceinline__ T load_global(const uint8_t* base, uint32_t off) {
+    global_ptr<uint8_t> b = reinterpret_cast<global_ptr<uint8_t>>(reinterpret_cast<uintptr_t>(base));
+    return *reinterpret_cast<global_ptr<T>>(b + off);
+}
+template <typename T>
+__device__ __forceinline__ T load_lds(uint32_t addr) {
+    return *reinterpret_cast<lds_ptr<const T>>(static_cast<uintptr_t>(addr));
+}
+template <typename T>
+__device__ __forceinline__ void store_lds(uint32_t addr, T v) {
+    *reinterpret_cast<lds_ptr<T>>(static_cast<uintptr_t>(addr)) = v;
+}
+
+// base | byte K of x, in one VALU instruction (sub-dword operand select)
+template <int K>
+__device__ __forceinline__ uint32_t or_byte(uint32_t base, uint32_t x) {
+    uint32_t r;
+    if constexpr (K == 0)
+        asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(base), "v"(x));
+    else if constexpr (K == 1)
+        asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(base), "v"(x));
+    else if constexpr (K == 2)
+        asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(base), "v"(x));
+    else
+        asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(base), "v"(x));
+    return r;
+}
+
+// a uniform float the compiler cannot constant-fold, so x * w + acc with fp16 x stays one
+// mixed-precision FMA also for w == 1
+__device__ __forceinline__ float opaque(float v) {
+    asm("" : "+s"(v));
+    return v;
+}
+
+// Buffer resource over a wave-uniform base: loads then take a 32-bit per-lane offset (constant for
+// the whole kernel) plus a scalar offset (the tile), so streaming costs no address arithmetic.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr int kStreamAux = 2;  // non-temporal: weights are read once, keep them from evicting the tables in L2
+__device__ __forceinline__ rsrc_t make_rsrc(const uint8_t* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, 0xFFFFFFFFu, 0x00020000);
+}
+
 template <int B, int NP, int GQ, bool HZ>
-__device__ __forceinline__ void issue_tile(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, const uint8_t* tile,
-                                           const uint8_t* lut_t, const uint8_t* lut_s, int kt, int lane) {
+__device__ __forceinline__ void issue_tile(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, rsrc_t rw, rsrc_t rt,
+                                           rsrc_t rs, int kt, int lane) {
     using Cfg = GemvCfg<B, NP, GQ, HZ>;
+    const int so = kt * Cfg::TB;  // scalar offset of the tile block inside the row block
 #pragma unroll
-    for (int v = 0; v < B; ++v) s.c[v] = *reinterpret_cast<const u32x4*>(tile + v * 1024 + lane * 16);
-    const uint8_t* mp = tile + B * 1024 + lane * Cfg::MPL;
+    for (int v = 0; v < B; ++v) s.c[v] = __builtin_amdgcn_raw_buffer_load_b128(rw, v * 1024 + lane * 16, so, kStreamAux);
+    const int mo = B * 1024 + lane * Cfg::MPL;
     if constexpr (Cfg::MPL == 2) {
-        s.meta[0] = *reinterpret_cast<const uint16_t*>(mp);
+        s.meta[0] = __builtin_amdgcn_raw_buffer_load_b16(rw, mo, so, kStreamAux);
     } else if constexpr (Cfg::MPL == 4) {
-        s.meta[0] = *reinterpret_cast<const uint32_t*>(mp);
+        s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rw, mo, so, kStreamAux);
     } else if constexpr (Cfg::MPL == 8) {
-        u32x2 v = *reinterpret_cast<const u32x2*>(mp);
+        u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rw, mo, so, kStreamAux);
         s.meta[0] = v.x;
         s.meta[1] = v.y;
     } else {
-        u32x4 v = *reinterpret_cast<const u32x4*>(mp);
+        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, mo, so, kStreamAux);
         s.meta[0] = v.x;
         s.meta[1] = v.y;
         s.meta[2] = v.z;
         s.meta[3] = v.w;
     }
-    const uint8_t* ts = lut_t + (size_t)kt * Cfg::T_BYTES;
+    const int to = kt * Cfg::T_BYTES;
 #pragma unroll
-    for (int q = 0; q < NP; ++q) s.tt[q] = *reinterpret_cast<const u32x4*>(ts + q * 1024 + lane * 16);
+    for (int q = 0; q < NP; ++q) s.tt[q] = __builtin_amdgcn_raw_buffer_load_b128(rt, q * 1024 + lane * 16, to, 0);
     s.sv = 0.f;
-    if (lane < Cfg::S_FLOATS) s.sv = reinterpret_cast<const float*>(lut_s)[(size_t)kt * Cfg::S_FLOATS + lane];
+    if (lane < Cfg::S_FLOATS)
+        s.sv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, lane * 4, kt * Cfg::S_FLOATS * 4, 0));
 }
 
-// Lookups of one tile block for the lane's row.  `lds` is the wave's private slot.
+// A table entry as it comes out of LDS: NP fp16 values (the NP tokens of one pattern).
+template <int NP> struct EntryT;
+template <> struct EntryT<1> { typedef _Float16 type; };
+template <> struct EntryT<2> { typedef half2_t type; };
+template <> struct EntryT<4> { typedef half4_t type; };
+template <> struct EntryT<8> { typedef half8_t type; };
+
+template <int NP>
+__device__ __forceinline__ void accumulate(const typename EntryT<NP>::type& e, float pw, float (&a)[NP]) {
+    if constexpr (NP == 1) {
+        a[0] = fmaf(pw, (float)e, a[0]);
+    } else {
+#pragma unroll
+        for (int n = 0; n < NP; ++n) a[n] = fmaf(pw, (float)e[n], a[n]);
+    }
+}
+
+// Lookups of one tile block for the lane's row.  `lds` is the LDS address of the wave's private slot
+// (a multiple of 256, so index bits can be OR-ed in).  The 4*B plane words of the tile are handled
+// one after the other, software pipelined: the eight lookups of word w+1 are issued before the eight
+// results of word w are accumulated, so LDS latency overlaps the arithmetic with few live registers.
 template <int B, int NP, int GQ, bool HZ>
-__device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, uint8_t* lds, int lane,
-                                             float (&y)[NP]) {
+__device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, uint32_t lds, int lane,
+                                             const float (&pw)[B], float (&y)[NP]) {
     using Cfg = GemvCfg<B, NP, GQ, HZ>;
+    typedef typename EntryT<NP>::type entry_t;
+    constexpr int EB = 2 * NP;                                       // bytes per table entry
+    constexpr int SH = EB == 2 ? 1 : EB == 4 ? 2 : EB == 8 ? 3 : 4;  // log2(EB)
+    constexpr uint32_t NIB = 0x0F0F0F0Fu << SH;                      // index * EB, one per byte
+    constexpr int TSTRIDE = 16 * EB;                                 // bytes per table
+    constexpr int W = 4 * B;                                         // plane words per tile
+    constexpr int WPG = (GQ / 32) * B;                               // plane words per quantization block
     // table slice and group sums -> LDS (wave private; LDS operations of one wave execute in order)
     wave_lds_sync();  // every lane is done reading the previous slice
 #pragma unroll
-    for (int q = 0; q < NP; ++q) *reinterpret_cast<u32x4*>(lds + q * 1024 + lane * 16) = s.tt[q];
-    float* sl = reinterpret_cast<float*>(lds + Cfg::T_BYTES);
-    if (lane < Cfg::S_FLOATS) sl[lane] = s.sv;
+    for (int q = 0; q < NP; ++q) store_lds<u32x4>(lds + q * 1024 + lane * 16, s.tt[q]);
+    if (lane < Cfg::S_FLOATS) store_lds<float>(lds + Cfg::T_BYTES + lane * 4, s.sv);
     wave_lds_sync();
 
+    uint32_t base_v = lds;
+    asm("" : "+v"(base_v));  // the sub-dword OR wants its operands in vector registers
+
+    // word wi: 32-weight block kb32 = wi / B of the tile, bit-plane i = wi % B
+    auto fetch = [&](int wi, entry_t (&e)[8]) {
+        const int kb32 = wi / B, i = wi % B;
+        const int v = (kb32 * 32) / Cfg::CH;
+        const int ksub = ((kb32 * 32) % Cfg::CH) / 32;
+        const int tb = (kb32 * 8) * TSTRIDE;  // the 8 tables of this block
+        const uint32_t w = word_of(s.c[v], ksub * B + i);
+        // the eight 4-bit indices of the word, pre-multiplied by the entry size: even nibbles in the
+        // bytes of xe, odd nibbles in the bytes of xo
+        const uint32_t xe = (w << SH) & NIB;
+        const uint32_t xo = SH == 4 ? (w & NIB) : ((w >> (4 - SH)) & NIB);
+        e[0] = load_lds<entry_t>(or_byte<0>(base_v, xe) + (tb + 0 * TSTRIDE));
+        e[1] = load_lds<entry_t>(or_byte<0>(base_v, xo) + (tb + 1 * TSTRIDE));
+        e[2] = load_lds<entry_t>(or_byte<1>(base_v, xe) + (tb + 2 * TSTRIDE));
+        e[3] = load_lds<entry_t>(or_byte<1>(base_v, xo) + (tb + 3 * TSTRIDE));
+        e[4] = load_lds<entry_t>(or_byte<2>(base_v, xe) + (tb + 4 * TSTRIDE));
+        e[5] = load_lds<entry_t>(or_byte<2>(base_v, xo) + (tb + 5 * TSTRIDE));
+        e[6] = load_lds<entry_t>(or_byte<3>(base_v, xe) + (tb + 6 * TSTRIDE));
+        e[7] = load_lds<entry_t>(or_byte<3>(base_v, xo) + (tb + 7 * TSTRIDE));
+    };
+
+    entry_t e[2][8];
+    float a[NP];
+    fetch(0, e[0]);
 #pragma unroll
-    for (int gi = 0; gi < Cfg::GPT; ++gi) {
-        float a[NP];
+    for (int wi = 0; wi < W; ++wi) {
+        if (wi + 1 < W) fetch(wi + 1, e[(wi + 1) & 1]);
+        if (wi % WPG == 0) {
 #pragma unroll
-        for (int n = 0; n < NP; ++n) a[n] = 0.f;
+            for (int n = 0; n < NP; ++n) a[n] = 0.f;
+        }
 #pragma unroll
-        for (int kb = 0; kb < GQ / 32; ++kb) {
-            const int kb32 = gi * (GQ / 32) + kb;  // 32-weight block inside the tile
-            const int v = (kb32 * 32) / Cfg::CH;
-            const int ksub = ((kb32 * 32) % Cfg::CH) / 32;
-            const uint8_t* tb = lds + (kb32 * 8) * 16 * NP * 2;  // 8 tables of this block
+        for (int u = 0; u < 8; ++u) accumulate<NP>(e[wi & 1][u], pw[wi % B], a);
+        if (wi % WPG == WPG - 1) {
+            // scale and zero of the quantization block just finished
+            const int gi = wi / WPG;
+            const int mo = gi * Cfg::MSZ;
+            const uint32_t mw = s.meta[mo / 4];
+            const float sc = half_bits_to_float((mo % 4) ? (mw >> 16) : (mw & 0xffffu));
+            const uint32_t sg = lds + Cfg::T_BYTES + gi * NP * 4;
+            if constexpr (HZ) {
+                const float z = half_bits_to_float(mw >> 16);  // 4-byte entry: scale low, zero high
 #pragma unroll
-            for (int i = 0; i < B; ++i) {
-                const uint32_t w = word_of(s.c[v], ksub * B + i);
-                const float pw = (float)(1 << i);  // the plane's weight: "shift and accumulate"
+                for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(-z, load_lds<float>(sg + n * 4), a[n]), y[n]);
+            } else {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const uint32_t idx = (w >> (4 * u)) & 15u;
-                    const uint8_t* ep = tb + (u * 16 + idx) * NP * 2;
-                    if constexpr (NP == 1) {
-                        a[0] = fmaf(pw, (float)*reinterpret_cast<const _Float16*>(ep), a[0]);
-                    } else if constexpr (NP == 2) {
-                        half2_t e = *reinterpret_cast<const half2_t*>(ep);
-                        a[0] = fmaf(pw, (float)e.x, a[0]);
-                        a[1] = fmaf(pw, (float)e.y, a[1]);
-                    } else if constexpr (NP == 4) {
-                        half4_t e = *reinterpret_cast<const half4_t*>(ep);
-#pragma unroll
-                        for (int n = 0; n < 4; ++n) a[n] = fmaf(pw, (float)e[n], a[n]);
-                    } else {
-                        half8_t e = *reinterpret_cast<const half8_t*>(ep);
-#pragma unroll
-                        for (int n = 0; n < 8; ++n) a[n] = fmaf(pw, (float)e[n], a[n]);
-                    }
-                }
+                for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(2.f, a[n], -load_lds<float>(sg + n * 4)), y[n]);
             }
         }
-        // scale and zero of this quantization block
-        const int mo = gi * Cfg::MSZ;
-        const uint32_t mw = s.meta[mo / 4];
-        const float sc = half_bits_to_float((mo % 4) ? (mw >> 16) : (mw & 0xffffu));
-        const float* sg = sl + gi * NP;
-        if constexpr (HZ) {
-            const float z = half_bits_to_float(mw >> 16);  // 4-byte entry: scale low, zero high
-#pragma unroll
-            for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(-z, sg[n], a[n]), y[n]);
-        } else {
-#pragma unroll
-            for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(2.f, a[n], -sg[n]), y[n]);
-        }
+        __builtin_amdgcn_sched_barrier(0);  // keep the pipeline order: bounds the live registers
     }
 }
 
@@ -228,12 +321,15 @@ template <int B, int NP, int GQ, bool HZ, bool SINGLE>
 __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> a) {
     using Cfg = GemvCfg<B, NP, GQ, HZ>;
     constexpr int D = Cfg::D;
-    __shared__ __attribute__((aligned(16))) uint8_t slots[kWaves * Cfg::SLOT];
+    __shared__ __attribute__((aligned(1024))) uint8_t slots[kWaves * Cfg::SLOT];
     __shared__ float red[kWaves][NP][kRows];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    uint8_t* lds = slots + wave * Cfg::SLOT;
+    const uint32_t lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)slots)) + wave * Cfg::SLOT;
+    float pw[B];  // plane weights 2^i: "shift and accumulate"
+#pragma unroll
+    for (int i = 0; i < B; ++i) pw[i] = opaque((float)(1 << i));
 
     // which GEMV does this workgroup belong to: binary search over the first-workgroup indices
     int g = 0;
@@ -246,22 +342,23 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
         g = lo;
     }
     const GemvDesc& d = desc_of<SINGLE>(a, g);
-    const int n_seg = d.n_seg, n_ktiles = d.n_ktiles;
-    const int wg_local = (int)blockIdx.x - d.wg_begin;
+    const int n_seg = uniform(d.n_seg), n_ktiles = uniform(d.n_ktiles);
+    const int wg_local = (int)blockIdx.x - uniform(d.wg_begin);
     const int rb = wg_local / n_seg, seg = wg_local % n_seg;
-    const int k0 = seg * d.seg_tiles;
-    const int k1 = min(k0 + d.seg_tiles, n_ktiles);
+    const int seg_tiles = uniform(d.seg_tiles);
+    const int k0 = seg * seg_tiles;
+    const int k1 = min(k0 + seg_tiles, n_ktiles);
     const int per_wave = (k1 - k0 + kWaves - 1) / kWaves;
     const int t0 = min(k0 + wave * per_wave, k1);  // this wave's K tiles [t0, t1)
     const int t1 = min(t0 + per_wave, k1);
-    const uint8_t* tiles = d.tiles + (size_t)rb * n_ktiles * Cfg::TB;
-    const uint8_t* lut_t = d.lut_t;
-    const uint8_t* lut_s = d.lut_s;
+    const rsrc_t rw = make_rsrc(uniform(d.tiles) + (size_t)rb * n_ktiles * Cfg::TB);  // this row block's tiles
+    const rsrc_t rt = make_rsrc(uniform(d.lut_t));
+    const rsrc_t rs = make_rsrc(uniform(d.lut_s));
 
     Stage<B, NP, Cfg::MPL> st[D] = {};
 #pragma unroll
     for (int s = 0; s < D; ++s)
-        if (t0 + s < t1) issue_tile<B, NP, GQ, HZ>(st[s], tiles + (size_t)(t0 + s) * Cfg::TB, lut_t, lut_s, t0 + s, lane);
+        if (t0 + s < t1) issue_tile<B, NP, GQ, HZ>(st[s], rw, rt, rs, t0 + s, lane);
 
     float y[NP];
 #pragma unroll
@@ -272,9 +369,17 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
         for (int s = 0; s < D; ++s) {
             const int t = base + s;
             if (t < t1) {
-                consume_tile<B, NP, GQ, HZ>(st[s], lds, lane, y);
+                {   // the more tiles a wave still has to do, the higher its issue priority: the waves
+                    // of a SIMD then finish together instead of leaving the youngest to run alone
+                    const int rem = t1 - t;
+                    if (rem >= 7) __builtin_amdgcn_s_setprio(3);
+                    else if (rem >= 5) __builtin_amdgcn_s_setprio(2);
+                    else if (rem >= 3) __builtin_amdgcn_s_setprio(1);
+                    else __builtin_amdgcn_s_setprio(0);
+                }
+                consume_tile<B, NP, GQ, HZ>(st[s], lds, lane, pw, y);
                 if (t + D < t1)
-                    issue_tile<B, NP, GQ, HZ>(st[s], tiles + (size_t)(t + D) * Cfg::TB, lut_t, lut_s, t + D, lane);
+                    issue_tile<B, NP, GQ, HZ>(st[s], rw, rt, rs, t + D, lane);
             }
         }
     }

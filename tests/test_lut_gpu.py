@@ -47,3 +47,19 @@ def test_tables_and_group_sums(oracle_lib, N, K, group):
     allT = raw[: nkt * 1024 * NP].view(np.float16).reshape(nkt * 32, 16, NP)
     assert np.all(allT[:, :, N:] == 0)
     assert np.all(allT[K // 4:, :, :] == 0)
+
+
+def test_batched_build_matches_single_calls(oracle_lib):
+    """One launch for several activations writes the same bytes as separate calls."""
+    import paper_2511_11248_amd as tman
+    from gpu_helpers import dev, to_dev
+
+    N, group = 3, 64
+    Ks = [512, 4096, 11008, 64]
+    xs = [to_dev(synth.normal_fp16(990 + i, N * K).reshape(N, K)) for i, K in enumerate(Ks)]
+    single = [build_lut(x, group) for x in xs]
+    luts = [torch.full((tman.tman_lut_bytes(N, K, group),), 0x77, dtype=torch.uint8, device=dev()) for K in Ks]
+    tman.tman_build_lut_batch(xs, N, Ks, group, luts)
+    torch.cuda.synchronize()
+    for a, b in zip(single, luts):
+        assert torch.equal(a, b)
