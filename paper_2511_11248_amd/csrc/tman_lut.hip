@@ -13,8 +13,8 @@
 // so the slice of one K tile is contiguous and can be copied to LDS as it is.
 //
 // One launch serves up to 16 activations (the distinct inputs of a decode step): every workgroup
-// finds its activation by its block index, the first blocks of an activation build tables (one
-// thread per table and token), the rest build the group sums (one thread per group and token).
+// finds its activation by its block index; a thread builds one table of one token and takes part in
+// the sum of its quantization block.
 #include <hip/hip_fp16.h>
 
 #include "tman_internal.h"
@@ -25,56 +25,67 @@ struct LutJob {
     const _Float16* x;
     _Float16* T;
     float* S;
-    int K, n_tables, n_groups;
-    int table_blocks;  // blocks that build tables; the group-sum blocks follow
-    int block_begin;   // first block of this activation in the launch
+    int K, n_tables;
+    int block_begin;  // first block of this activation in the launch
 };
 struct LutJobs {
     LutJob job[16];
     int count, N, NP, group;
 };
 
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+
+// One thread per (table j, token n).  Consecutive lanes own consecutive tables of one token, so the
+// group sum of a quantization block (group / 4 tables) is a butterfly over adjacent lanes.
 __global__ void __launch_bounds__(256) build_lut_kernel(LutJobs a) {
     int ji = 0;
 #pragma unroll 1
     for (int i = 1; i < a.count; ++i)
         if ((int)blockIdx.x >= a.job[i].block_begin) ji = i;
     const LutJob& jb = a.job[ji];
-    const int block = (int)blockIdx.x - jb.block_begin;
     const int N = a.N, NP = a.NP, K = jb.K;
-    if (block < jb.table_blocks) {
-        const int tid = block * 256 + threadIdx.x;
-        if (tid >= jb.n_tables * NP) return;
-        const int j = tid / NP, n = tid % NP;
-        float v[4] = {0.f, 0.f, 0.f, 0.f};
-        if (n < N) {
+    const int tid = ((int)blockIdx.x - jb.block_begin) * 256 + threadIdx.x;
+    const int n = tid / jb.n_tables, j = tid % jb.n_tables;  // n_tables is a multiple of 32
+    const bool live = n < NP;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (live && n < N) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int k = 4 * j + t;
-                if (k < K) v[t] = (float)jb.x[(size_t)n * K + k];
-            }
+        for (int t = 0; t < 4; ++t) {
+            const int k = 4 * j + t;
+            if (k < K) v[t] = (float)jb.x[(size_t)n * K + k];
         }
-        _Float16* dst = jb.T + ((size_t)j * 16) * NP + n;
-#pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            float s = 0.f;
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-                if ((p >> t) & 1) s += v[t];
-            dst[(size_t)p * NP] = (_Float16)s;  // round to nearest even
-        }
-    } else {
-        const int tid = (block - jb.table_blocks) * 256 + threadIdx.x;
-        if (tid >= jb.n_groups * NP) return;
-        const int G = tid / NP, n = tid % NP;
-        float s = 0.f;
-        if (n < N) {
-            const int k0 = G * a.group;
-            for (int t = 0; t < a.group; ++t)
-                if (k0 + t < K) s += (float)jb.x[(size_t)n * K + k0 + t];
-        }
-        jb.S[(size_t)G * NP + n] = s;
     }
+    _Float16 e[16];
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+        float s = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if ((p >> t) & 1) s += v[t];
+        e[p] = (_Float16)s;  // round to nearest even
+    }
+    if (live) {
+        if (NP == 1) {
+            half8_t lo, hi;
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                lo[p] = e[p];
+                hi[p] = e[p + 8];
+            }
+            half8_t* dst = reinterpret_cast<half8_t*>(jb.T + (size_t)j * 16);
+            dst[0] = lo;
+            dst[1] = hi;
+        } else {
+            _Float16* dst = jb.T + ((size_t)j * 16) * NP + n;
+#pragma unroll
+            for (int p = 0; p < 16; ++p) dst[(size_t)p * NP] = e[p];
+        }
+    }
+    // group sums: add the four activations, then the group / 4 tables of the block
+    float s = (v[0] + v[1]) + (v[2] + v[3]);
+    const int tables_per_group = a.group / kLutGroup;  // 8, 16 or 32: within one wave
+    for (int d = 1; d < tables_per_group; d <<= 1) s += __shfl_xor(s, d, 64);
+    if (live && (j % tables_per_group) == 0) jb.S[(size_t)(j / tables_per_group) * NP + n] = s;
 }
 
 int launch_build_lut_batch(int count, const void* const* x, int N, const int* K, int group, void* const* lut,
@@ -96,10 +107,8 @@ int launch_build_lut_batch(int count, const void* const* x, int N, const int* K,
             jb.S = reinterpret_cast<float*>(static_cast<uint8_t*>(lut[src]) + (size_t)nkt * kTableBytesPerKTile * NP);
             jb.K = K[src];
             jb.n_tables = nkt * kTablesPerKTile;
-            jb.n_groups = nkt * (kKTile / group);
-            jb.table_blocks = (jb.n_tables * NP + 255) / 256;
             jb.block_begin = blocks;
-            if (i < a.count) blocks += jb.table_blocks + (jb.n_groups * NP + 255) / 256;
+            if (i < a.count) blocks += (jb.n_tables * NP + 255) / 256;
         }
         hipLaunchKernelGGL(build_lut_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
     }
