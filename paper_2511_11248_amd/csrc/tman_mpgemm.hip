@@ -14,9 +14,8 @@
 //            fp16( (1024 + c) * scale - (1024 + zero) * scale ) evaluated in fp32 with a single rounding,
 //            with the per-block constants (scale, -(1024 + zero) * scale) computed once per block.
 //            A lookup per weight in LDS would compete with the MFMA operand reads for LDS bandwidth.
-// The fp16 weight tile goes to LDS and is shared by the four waves of the workgroup (each weight is
-// dequantized once per 256 tokens); activations are staged next to it in the k order level 1
-// produces.  Pipeline (the GPU form of DMA -> vector -> matrix): global loads of stage s+2 are in
+// The fp16 weight tile goes to LDS and is shared by the waves of the workgroup (each weight is
+// dequantized once per 256 tokens); activations are staged next to it unchanged.  Pipeline (the GPU form of DMA -> vector -> matrix): global loads of stage s+2 are in
 // flight while stage s+1 is dequantized into the other LDS buffer and stage s feeds
 // v_mfma_f32_32x32x16_f16 (fp32 accumulation); one barrier per stage.
 #include <hip/hip_fp16.h>
@@ -47,9 +46,26 @@ struct GemmArgs {
     int M, N, K, n_row_blocks, n_ktiles;
 };
 
-__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+// raw buffer resource: loads at or beyond `bytes` return zero
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
 
-// Level 1: bit planes of 32 weights -> four words of eight 4-bit codes; word o, field f = weight 4f + o.
+// (a & mask) | (b & ~mask) and (a & mask) | k as single instructions; the masks live in scalar registers
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
+    uint32_t d;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "s"(mask), "v"(a), "v"(b));
+    return d;
+}
+__device__ __forceinline__ uint32_t and_or(uint32_t a, uint32_t mask, uint32_t k) {
+    uint32_t d;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(mask), "v"(k));
+    return d;
+}
+
+// Level 1: bit planes of 32 weights -> four words of eight 4-bit fields; word o, field f = weight 4f + o.
+// For fewer than four planes the upper bits of a field hold bits of other weights; level 2 masks them.
 template <int B>
 __device__ __forceinline__ void planes_to_codes(const uint32_t (&p)[B], uint32_t (&out)[4]) {
     if constexpr (B == 4) {
@@ -65,13 +81,13 @@ __device__ __forceinline__ void planes_to_codes(const uint32_t (&p)[B], uint32_t
     } else if constexpr (B == 2) {
         const uint32_t a = bfi(0x55555555u, p[0], p[1] << 1);
         const uint32_t b = bfi(0xAAAAAAAAu, p[1], p[0] >> 1);
-        out[0] = a & 0x33333333u;
-        out[2] = (a >> 2) & 0x33333333u;
-        out[1] = b & 0x33333333u;
-        out[3] = (b >> 2) & 0x33333333u;
+        out[0] = a;
+        out[2] = a >> 2;
+        out[1] = b;
+        out[3] = b >> 2;
     } else {
 #pragma unroll
-        for (int o = 0; o < 4; ++o) out[o] = (p[0] >> o) & 0x11111111u;
+        for (int o = 0; o < 4; ++o) out[o] = p[0] >> o;
     }
 }
 
@@ -82,127 +98,122 @@ struct WRegs {
     uint32_t meta;  // scale (low 16 bits) and zero (high 16 bits) of the block's quantization group
 };
 
+// Loads 32-weight block `kb32` of tile block `tile` of this wave's row block.  `rw` covers the row
+// block's tiles or nothing (rows beyond M, stages beyond K), in which case everything reads as zero.
 template <int B, int GQ, bool HZ>
-__device__ __forceinline__ void load_w(WRegs<B>& r, const uint8_t* tile, int kb32, int lane, bool valid) {
+__device__ __forceinline__ void load_w(WRegs<B>& r, rsrc_t rw, int tile, int kb32, int lane) {
     constexpr int CH = kKTile / B;
     constexpr int MSZ = HZ ? 4 : 2;
     constexpr int MPL = (kKTile / GQ) * MSZ;
-    // kb32: 32-weight block inside the 128-column tile block
+    constexpr int TB = B * 1024 + 64 * MPL;
     const int v = (kb32 * 32) / CH, ksub = ((kb32 * 32) % CH) / 32;
-    const uint8_t* p = tile + v * 1024 + lane * 16 + ksub * B * 4;
-    if (!valid) {
-#pragma unroll
-        for (int i = 0; i < B; ++i) r.plane[i] = 0u;
-        r.meta = 0u;
-        return;
-    }
+    const int so = tile * TB + v * 1024 + ksub * B * 4;
     if constexpr (B == 4) {
-        const u32x4 w = *reinterpret_cast<const u32x4*>(p);
+        const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rw, lane * 16, so, 0);
         r.plane[0] = w.x; r.plane[1] = w.y; r.plane[2] = w.z; r.plane[3] = w.w;
     } else if constexpr (B == 2) {
-        const u32x2 w = *reinterpret_cast<const u32x2*>(p);
+        const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rw, lane * 16, so, 0);
         r.plane[0] = w.x; r.plane[1] = w.y;
     } else {
-        r.plane[0] = *reinterpret_cast<const uint32_t*>(p);
+        r.plane[0] = __builtin_amdgcn_raw_buffer_load_b32(rw, lane * 16, so, 0);
     }
-    const int gi = (kb32 * 32) / GQ;
-    const uint8_t* mp = tile + B * 1024 + lane * MPL + gi * MSZ;
-    if constexpr (HZ) r.meta = *reinterpret_cast<const uint32_t*>(mp);
-    else r.meta = *reinterpret_cast<const uint16_t*>(mp);
+    const int mo = tile * TB + B * 1024 + ((kb32 * 32) / GQ) * MSZ;
+    if constexpr (HZ) r.meta = __builtin_amdgcn_raw_buffer_load_b32(rw, lane * MPL, mo, 0);
+    else r.meta = __builtin_amdgcn_raw_buffer_load_b16(rw, lane * MPL, mo, 0);
 }
 
-// Level 2 for one lane's 32 weights; writes them as fp16 into its row of the LDS weight tile
-// (`wrow` already points at the block's 64 bytes).
+// Level 2 for one lane's 32 weights; writes them as fp16, in column order, into its row of the LDS
+// weight tile (`wrow` already points at the block's 64 bytes).
+//
+// Field f of code word o (weight 4f + o) is turned into an fp16 number without moving it to bit 0:
+// a nibble at mantissa bits 0..3 of 0x6400 reads 1024 + c, one at bits 4..7 reads 1024 + 16c.  Fields
+// f and f + 4 sit 16 bits apart, so one AND-OR makes two such numbers; a single shift by 8 brings
+// fields 2, 3, 6, 7 into reach.  The affine map (c - zero) * scale is then one fp32 FMA per weight
+// with a single rounding to fp16:  (1024 + c) * s - (1024 + z) * s   or   (1024 + 16c) * s/16 - (64 + z) * s.
+// The FMA writes either half of its destination, which puts weights 4f + o and 4f + o + 1 (from the
+// same field of two code words) side by side at no cost.
 template <int B, bool HZ>
-__device__ __forceinline__ void dequant_to_lds(const WRegs<B>& r, uint8_t* wrow) {
+struct Dequant {
     uint32_t codes[4];
-    planes_to_codes<B>(r.plane, codes);
-    const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)(r.meta & 0xffffu));
-    float mul, bias;  // weight = (1024 + c) * mul + bias, one rounding to fp16
-    if constexpr (HZ) {
-        const float z = (float)__builtin_bit_cast(_Float16, (uint16_t)(r.meta >> 16));
-        mul = s;
-        bias = -(1024.f + z) * s;
-    } else {
-        mul = 2.f * s;  // (2c - 1) * s
-        bias = -2049.f * s;
-    }
-#pragma unroll
-    for (int o = 0; o < 4; ++o) {
-        u32x4 out;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            // codes of weights 4d + o and 4(d+4) + o, each inserted into the mantissa of 1024.0
-            const uint32_t pair = ((codes[o] >> (4 * d)) & 0x000F000Fu) | 0x64006400u;
-            const half2_t v = __builtin_bit_cast(half2_t, pair);
-            half2_t w;
-            w.x = (_Float16)fmaf((float)v.x, mul, bias);
-            w.y = (_Float16)fmaf((float)v.y, mul, bias);
-            out[d] = __builtin_bit_cast(uint32_t, w);
+    float mul[2], bias[2];  // [0]: nibble at mantissa bits 0..3, [1]: at bits 4..7
+    half2_t P[4][4];        // [o][d]: halves = fields d and d + 4 of code word o, as 1024 + c or 1024 + 16c
+
+    // part 1: level 1 and the block's constants
+    __device__ __forceinline__ void start(const WRegs<B>& r) {
+        planes_to_codes<B>(r.plane, codes);
+        const float s = (float)__builtin_bit_cast(_Float16, (uint16_t)(r.meta & 0xffffu));
+        if constexpr (HZ) {
+            const float z = (float)__builtin_bit_cast(_Float16, (uint16_t)(r.meta >> 16));
+            mul[0] = s;
+            bias[0] = -(1024.f + z) * s;
+            mul[1] = s * 0.0625f;
+            bias[1] = -(64.f + z) * s;
+        } else {
+            mul[0] = 2.f * s;  // (2c - 1) * s
+            bias[0] = -2049.f * s;
+            mul[1] = s * 0.125f;
+            bias[1] = -129.f * s;
         }
-        *reinterpret_cast<u32x4*>(wrow + o * 16) = out;
     }
-}
-
-// activation staging: a unit = one token row, one 32-column block, one pair of 8-column pieces
-// (columns 8pp..8pp+7 and 16+8pp..16+8pp+7); two units per thread and stage
-struct XRegs {
-    u32x4 p[2], q[2];
-};
-struct XPlan {
-    const _Float16* src[2];  // first piece of each unit at stage 0 (nullptr: token beyond N)
-    int col[2];              // its column
-    int dst[2];              // byte offset of the unit inside the LDS activation tile
-};
-
-__device__ __forceinline__ void plan_x(XPlan& pl, const GemmArgs& a, int n0, int tid) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int u = i * 512 + tid;
-        const int n = u >> 2, blk = (u >> 1) & 1, pp = u & 1;
-        pl.col[i] = blk * 32 + pp * 8;
-        pl.src[i] = (n0 + n < a.N) ? a.x + (size_t)(n0 + n) * a.K + pl.col[i] : nullptr;
-        pl.dst[i] = n * kRowBytes + (blk * 32 + 4 * pp) * 2;
-    }
-}
-
-__device__ __forceinline__ void load_x(XRegs& r, const XPlan& pl, int K, int k0) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        u32x4 P = {0u, 0u, 0u, 0u}, Q = {0u, 0u, 0u, 0u};
-        if (pl.src[i]) {
-            const int gk = k0 + pl.col[i];  // K is a multiple of 32, so pieces are all-or-nothing
-            if (gk + 8 <= K) P = *reinterpret_cast<const u32x4*>(pl.src[i] + k0);
-            if (gk + 24 <= K) Q = *reinterpret_cast<const u32x4*>(pl.src[i] + k0 + 16);
-        }
-        r.p[i] = P;
-        r.q[i] = Q;
-    }
-}
-
-// Writes the units in the k order of the weight tile: column 4f + o of a 32-block sits at position
-// 8o + slot(f), slot(f) = 2f for f < 4, 2(f - 4) + 1 otherwise (the order dequant_to_lds emits).
-__device__ __forceinline__ void store_x(const XRegs& r, const XPlan& pl, uint8_t* xtile) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        uint8_t* dst = xtile + pl.dst[i];
-        const u32x4 P = r.p[i], Q = r.q[i];
-        // piece P holds f = 2pp (elements 0..3) and 2pp + 1 (elements 4..7); piece Q holds f + 4
-        const uint32_t pw[4] = {P.x, P.y, P.z, P.w}, qw[4] = {Q.x, Q.y, Q.z, Q.w};
+    // part 2: codes -> fp16 integers
+    __device__ __forceinline__ void insert() {
+        constexpr uint32_t kCodeMask = (1u << B) - 1u;
+        constexpr uint32_t kMaskLo = kCodeMask | (kCodeMask << 16), kMaskHi = kMaskLo << 4;
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
-            const uint32_t pa = pw[o >> 1], qa = qw[o >> 1], pb = pw[2 + (o >> 1)], qb = qw[2 + (o >> 1)];
-            u32x2 w;
-            if (o & 1) {
-                w.x = (pa >> 16) | (qa & 0xffff0000u);
-                w.y = (pb >> 16) | (qb & 0xffff0000u);
-            } else {
-                w.x = (pa & 0xffffu) | (qa << 16);
-                w.y = (pb & 0xffffu) | (qb << 16);
-            }
-            *reinterpret_cast<u32x2*>(dst + o * 16) = w;
+            const uint32_t c = codes[o], c8 = codes[o] >> 8;
+            P[o][0] = __builtin_bit_cast(half2_t, and_or(c, kMaskLo, 0x64006400u));
+            P[o][1] = __builtin_bit_cast(half2_t, and_or(c, kMaskHi, 0x64006400u));
+            P[o][2] = __builtin_bit_cast(half2_t, and_or(c8, kMaskLo, 0x64006400u));
+            P[o][3] = __builtin_bit_cast(half2_t, and_or(c8, kMaskHi, 0x64006400u));
         }
     }
+    // part 3: 16-byte piece q (weights 8q .. 8q + 7 = fields 2q, 2q + 1) -> LDS
+    __device__ __forceinline__ void emit(int q, uint8_t* wrow) const {
+        u32x4 out;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int f = 2 * q + (i >> 1), o = (i & 1) * 2, d = f & 3, t = d & 1;
+            const _Float16 va = (f >> 2) ? P[o][d].y : P[o][d].x;
+            const _Float16 vb = (f >> 2) ? P[o + 1][d].y : P[o + 1][d].x;
+            half2_t w;
+            w.x = (_Float16)fmaf((float)va, mul[t], bias[t]);
+            w.y = (_Float16)fmaf((float)vb, mul[t], bias[t]);
+            out[i] = __builtin_bit_cast(uint32_t, w);
+        }
+        *reinterpret_cast<u32x4*>(wrow + q * 16) = out;
+    }
+};
+
+template <int B, bool HZ>
+__device__ __forceinline__ void dequant_to_lds(const WRegs<B>& r, uint8_t* wrow) {
+    Dequant<B, HZ> dq;
+    dq.start(r);
+    dq.insert();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dq.emit(q, wrow);
+}
+
+// activation staging: plain 16-byte pieces (8 columns of one token), four per thread and stage;
+// eight consecutive lanes cover the 128 bytes of one token row
+struct XRegs {
+    u32x4 p[4];
+};
+constexpr int kXPieceStride = 64 * kRowBytes;  // pieces i and i + 1 of a thread are 64 tokens apart
+constexpr uint32_t kOutOfRange = 0x80000000u;
+
+// `rx` covers the workgroup's token rows from their first column (or nothing); rows beyond N lie
+// past its end.  k0: first column of the stage, col: first column of the thread's piece in the stage.
+__device__ __forceinline__ void load_x(XRegs& r, rsrc_t rx, const uint32_t (&voff)[4], int col, int K, int k0) {
+    const bool inside = col + 8 <= K - k0;  // K is a multiple of 32, so pieces are all-or-nothing
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        r.p[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, inside ? voff[i] : kOutOfRange, k0 * 2, 0);
+}
+
+__device__ __forceinline__ void store_x(const XRegs& r, uint8_t* dst) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(dst + i * kXPieceStride) = r.p[i];
 }
 
 template <int B, int GQ, bool HZ>
@@ -213,17 +224,25 @@ __global__ void __launch_bounds__(512, 1) mpgemm_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63, r = lane & 31, h = lane >> 5;
-    // eight waves: two per SIMD, so one wave's dequantization overlaps the other's MFMAs.
-    // MFMA part: wave (wm, wn) owns 128 rows x 64 tokens of the 256 x 256 tile.
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r = lane & 31, h = lane >> 5;
+    // eight waves, two per SIMD.  MFMA part: wave (wm, wn) owns 128 rows x 64 tokens of the 256 x 256 tile.
     const int wm = wave >> 2, wn = wave & 3;
     // dequantization part: wave owns row block (wave & 3) and 32-column block (wave >> 2) of each stage
     const int drb = wave & 3, dblk = wave >> 2;
     const int n0 = blockIdx.y * kTN;
     const int rbw = blockIdx.x * 4 + drb;
     const bool wvalid = rbw < a.n_row_blocks;
-    const uint8_t* wtiles = a.tiles + (size_t)(wvalid ? rbw : 0) * a.n_ktiles * TB;
-    const int n_stages = a.n_ktiles * 2;
+    const int n_stages = (a.K + kStageK - 1) / kStageK;
+    const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? rbw : 0) * a.n_ktiles * TB;
+    const int xrows = a.N - n0 < kTN ? a.N - n0 : kTN;
+    const _Float16* xsrc = a.x + (size_t)n0 * a.K;
+    const uint32_t xbytes = (uint32_t)xrows * (uint32_t)a.K * 2u;
+
+    const int xcol = (tid & 7) * 8;
+    uint32_t xvoff[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xvoff[i] = ((uint32_t)((tid >> 3) + 64 * i) * (uint32_t)a.K + (uint32_t)xcol) * 2u;
+    const int xdst = kWTile + (tid >> 3) * kRowBytes + (tid & 7) * 16;
     const int wdst = (drb * 64 + lane) * kRowBytes + dblk * 64;  // this lane's 64 bytes in the weight tile
 
     float16_t acc[4][2];
@@ -236,48 +255,75 @@ __global__ void __launch_bounds__(512, 1) mpgemm_kernel(GemmArgs a) {
 
     WRegs<B> wr;
     XRegs xr;
-    XPlan xp;
-    plan_x(xp, a, n0, tid);
+    // stage t: global -> registers; a stage beyond K reads zeros
+    auto load_stage_w = [&](int t) {
+        load_w<B, GQ, HZ>(wr, make_rsrc(wsrc, t < n_stages && wvalid ? 0x7fffffffu : 0u), t >> 1, 2 * (t & 1) + dblk, lane);
+    };
+    auto load_stage_x = [&](int t) {
+        load_x(xr, make_rsrc(xsrc, t < n_stages ? xbytes : 0u), xvoff, xcol, a.K, t * kStageK);
+    };
     // prologue: stage 0 straight into buffer 0, stage 1 into registers
-    load_w<B, GQ, HZ>(wr, wtiles, dblk, lane, wvalid);
-    load_x(xr, xp, a.K, 0);
+    load_stage_w(0);
+    load_stage_x(0);
     dequant_to_lds<B, HZ>(wr, smem + wdst);
-    store_x(xr, xp, smem + kWTile);
-    if (n_stages > 1) {
-        load_w<B, GQ, HZ>(wr, wtiles, 2 + dblk, lane, wvalid);
-        load_x(xr, xp, a.K, kStageK);
-    }
+    store_x(xr, smem + xdst);
+    load_stage_w(1);
+    load_stage_x(1);
     __syncthreads();
 
+    // MFMA operand addresses: lanes with h = 0 / 1 take the two 8-column groups of a 16-column step
+    const int wfrag = (wm * 128 + r) * kRowBytes + h * 16;
+    const int xfrag = kWTile + (wn * 64 + r) * kRowBytes + h * 16;
+
     for (int s = 0; s < n_stages; ++s) {
-        uint8_t* cur = smem + (s & 1) * kStageBytes;
-        uint8_t* nxt = smem + ((s + 1) & 1) * kStageBytes;
-        // stage s+1: registers -> LDS (the other buffer); stage s+2: global -> registers
-        if (s + 1 < n_stages) {
-            dequant_to_lds<B, HZ>(wr, nxt + wdst);
-            store_x(xr, xp, nxt + kWTile);
-        }
-        if (s + 2 < n_stages) {
-            const int s2 = s + 2;
-            load_w<B, GQ, HZ>(wr, wtiles + (size_t)(s2 >> 1) * TB, 2 * (s2 & 1) + dblk, lane, wvalid);
-            load_x(xr, xp, a.K, s2 * kStageK);
-        }
-        // stage s: four k16 steps; lanes with h = 0 / 1 take the two 8-column groups of a step
-        const uint8_t* wbase = cur + (wm * 128 + r) * kRowBytes + h * 16;
-        const uint8_t* xbase = cur + kWTile + (wn * 64 + r) * kRowBytes + h * 16;
+        const int cur_off = (s & 1) * kStageBytes;
+        uint8_t* cur = smem + cur_off;
+        uint8_t* nxt = smem + (kStageBytes - cur_off);
+        half8_t wf[2][4], xf[2][2];
+        auto read_frags = [&](int j) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            half8_t wf[4], xf[2];
+            for (int mb = 0; mb < 4; ++mb)
+                wf[j & 1][mb] = *reinterpret_cast<const half8_t*>(cur + wfrag + mb * 32 * kRowBytes + j * 32);
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb) wf[mb] = *reinterpret_cast<const half8_t*>(wbase + mb * 32 * kRowBytes + j * 32);
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) xf[nb] = *reinterpret_cast<const half8_t*>(xbase + nb * 32 * kRowBytes + j * 32);
+            for (int nb = 0; nb < 2; ++nb)
+                xf[j & 1][nb] = *reinterpret_cast<const half8_t*>(cur + xfrag + nb * 32 * kRowBytes + j * 32);
+        };
+        auto mfma_step = [&](int j) {
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[mb], xf[nb], acc[mb][nb], 0, 0, 0);
-        }
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[j & 1][mb], xf[j & 1][nb], acc[mb][nb], 0, 0, 0);
+        };
+        // One stage: the four 16-column MFMA steps of stage s alternate with the pieces of the work for
+        // later stages (stage s+1: registers -> fp16 -> the other LDS buffer; stage s+2: global ->
+        // registers).  The fences keep this order: a wave cannot overlap its own phases otherwise, and
+        // with short alternating pieces the two waves of a SIMD keep both the matrix and the vector pipe fed.
+        Dequant<B, HZ> dq;
+        read_frags(0);
+        store_x(xr, nxt + xdst);
+        load_stage_x(s + 2);
+        dq.start(wr);
+        load_stage_w(s + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(1);
+        mfma_step(0);
+        __builtin_amdgcn_sched_barrier(0);
+        dq.insert();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(2);
+        mfma_step(1);
+        __builtin_amdgcn_sched_barrier(0);
+        dq.emit(0, nxt + wdst);
+        dq.emit(1, nxt + wdst);
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(3);
+        mfma_step(2);
+        __builtin_amdgcn_sched_barrier(0);
+        dq.emit(2, nxt + wdst);
+        dq.emit(3, nxt + wdst);
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(3);
         __syncthreads();
     }
 
