@@ -194,56 +194,48 @@ __device__ __forceinline__ void dequant_to_lds(const WRegs<B>& r, uint8_t* wrow)
     for (int q = 0; q < 4; ++q) dq.emit(q, wrow);
 }
 
-// activation staging: plain 16-byte pieces (8 columns of one token), four per thread and stage;
-// eight consecutive lanes cover the 128 bytes of one token row
+// activation staging: plain 16-byte pieces (8 columns of one token), eight per producer thread and
+// stage; eight consecutive lanes cover the 128 bytes of one token row
+constexpr int kXPieces = 8;
 struct XRegs {
-    u32x4 p[4];
+    u32x4 p[kXPieces];
 };
-constexpr int kXPieceStride = 64 * kRowBytes;  // pieces i and i + 1 of a thread are 64 tokens apart
+constexpr int kXPieceStride = 32 * kRowBytes;  // pieces i and i + 1 of a thread are 32 tokens apart
 constexpr uint32_t kOutOfRange = 0x80000000u;
 
 // `rx` covers the workgroup's token rows from their first column (or nothing); rows beyond N lie
 // past its end.  k0: first column of the stage, col: first column of the thread's piece in the stage.
-__device__ __forceinline__ void load_x(XRegs& r, rsrc_t rx, const uint32_t (&voff)[4], int col, int K, int k0) {
+__device__ __forceinline__ void load_x(XRegs& r, rsrc_t rx, const uint32_t (&voff)[kXPieces], int col, int K, int k0) {
     const bool inside = col + 8 <= K - k0;  // K is a multiple of 32, so pieces are all-or-nothing
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < kXPieces; ++i)
         r.p[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, inside ? voff[i] : kOutOfRange, k0 * 2, 0);
 }
 
 __device__ __forceinline__ void store_x(const XRegs& r, uint8_t* dst) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(dst + i * kXPieceStride) = r.p[i];
+    for (int i = 0; i < kXPieces; ++i) *reinterpret_cast<u32x4*>(dst + i * kXPieceStride) = r.p[i];
 }
 
+// Workgroup = 12 waves, three per SIMD.  Waves 0..7 are consumers: wave (wm, wn) owns 128 rows x 64
+// tokens of the 256 x 256 tile and does nothing but read MFMA operands from LDS and issue MFMAs.
+// Waves 8..11 are producers: wave p turns row block p of each stage into fp16 in LDS and stages a
+// quarter of the activations.  Vector work of the producers and matrix work of the consumers come
+// from different waves of a SIMD, so the hardware overlaps them without any help from the schedule.
+constexpr int kConsumerWaves = 8;
+constexpr int kThreads = 768;
+
 template <int B, int GQ, bool HZ>
-__global__ void __launch_bounds__(512, 1) mpgemm_kernel(GemmArgs a) {
+__global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
     constexpr int MSZ = HZ ? 4 : 2;
     constexpr int TB = B * 1024 + 64 * (kKTile / GQ) * MSZ;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, r = lane & 31, h = lane >> 5;
-    // eight waves, two per SIMD.  MFMA part: wave (wm, wn) owns 128 rows x 64 tokens of the 256 x 256 tile.
-    const int wm = wave >> 2, wn = wave & 3;
-    // dequantization part: wave owns row block (wave & 3) and 32-column block (wave >> 2) of each stage
-    const int drb = wave & 3, dblk = wave >> 2;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int n0 = blockIdx.y * kTN;
-    const int rbw = blockIdx.x * 4 + drb;
-    const bool wvalid = rbw < a.n_row_blocks;
     const int n_stages = (a.K + kStageK - 1) / kStageK;
-    const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? rbw : 0) * a.n_ktiles * TB;
-    const int xrows = a.N - n0 < kTN ? a.N - n0 : kTN;
-    const _Float16* xsrc = a.x + (size_t)n0 * a.K;
-    const uint32_t xbytes = (uint32_t)xrows * (uint32_t)a.K * 2u;
-
-    const int xcol = (tid & 7) * 8;
-    uint32_t xvoff[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) xvoff[i] = ((uint32_t)((tid >> 3) + 64 * i) * (uint32_t)a.K + (uint32_t)xcol) * 2u;
-    const int xdst = kWTile + (tid >> 3) * kRowBytes + (tid & 7) * 16;
-    const int wdst = (drb * 64 + lane) * kRowBytes + dblk * 64;  // this lane's 64 bytes in the weight tile
 
     float16_t acc[4][2];
 #pragma unroll
@@ -252,85 +244,81 @@ __global__ void __launch_bounds__(512, 1) mpgemm_kernel(GemmArgs a) {
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mb][nb][v] = 0.f;
+    const int wm = (wave >> 2) & 1, wn = wave & 3, r = lane & 31, h = lane >> 5;
 
-    WRegs<B> wr;
-    XRegs xr;
-    // stage t: global -> registers; a stage beyond K reads zeros
-    auto load_stage_w = [&](int t) {
-        load_w<B, GQ, HZ>(wr, make_rsrc(wsrc, t < n_stages && wvalid ? 0x7fffffffu : 0u), t >> 1, 2 * (t & 1) + dblk, lane);
-    };
-    auto load_stage_x = [&](int t) {
-        load_x(xr, make_rsrc(xsrc, t < n_stages ? xbytes : 0u), xvoff, xcol, a.K, t * kStageK);
-    };
-    // prologue: stage 0 straight into buffer 0, stage 1 into registers
-    load_stage_w(0);
-    load_stage_x(0);
-    dequant_to_lds<B, HZ>(wr, smem + wdst);
-    store_x(xr, smem + xdst);
-    load_stage_w(1);
-    load_stage_x(1);
-    __syncthreads();
-
-    // MFMA operand addresses: lanes with h = 0 / 1 take the two 8-column groups of a 16-column step
-    const int wfrag = (wm * 128 + r) * kRowBytes + h * 16;
-    const int xfrag = kWTile + (wn * 64 + r) * kRowBytes + h * 16;
-
-    for (int s = 0; s < n_stages; ++s) {
-        const int cur_off = (s & 1) * kStageBytes;
-        uint8_t* cur = smem + cur_off;
-        uint8_t* nxt = smem + (kStageBytes - cur_off);
-        half8_t wf[2][4], xf[2][2];
-        auto read_frags = [&](int j) {
+    if (wave >= kConsumerWaves) {
+        // ---------------------------------------------------------------- producer
+        const int p = wave - kConsumerWaves, ptid = tid - kConsumerWaves * 64;
+        const int rbw = blockIdx.x * 4 + p;
+        const bool wvalid = rbw < a.n_row_blocks;
+        const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? rbw : 0) * a.n_ktiles * TB;
+        const int xrows = a.N - n0 < kTN ? a.N - n0 : kTN;
+        const _Float16* xsrc = a.x + (size_t)n0 * a.K;
+        const uint32_t xbytes = (uint32_t)xrows * (uint32_t)a.K * 2u;
+        const int xcol = (ptid & 7) * 8;
+        uint32_t xvoff[kXPieces];
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
-                wf[j & 1][mb] = *reinterpret_cast<const half8_t*>(cur + wfrag + mb * 32 * kRowBytes + j * 32);
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb)
-                xf[j & 1][nb] = *reinterpret_cast<const half8_t*>(cur + xfrag + nb * 32 * kRowBytes + j * 32);
+        for (int i = 0; i < kXPieces; ++i)
+            xvoff[i] = ((uint32_t)((ptid >> 3) + 32 * i) * (uint32_t)a.K + (uint32_t)xcol) * 2u;
+        const int xdst = kWTile + (ptid >> 3) * kRowBytes + (ptid & 7) * 16;
+        const int wdst = (p * 64 + lane) * kRowBytes;  // this lane's 128 bytes in the weight tile
+
+        WRegs<B> wr[2];
+        XRegs xr;
+        // stage t: global -> registers; a stage beyond K reads zeros
+        auto load_stage = [&](int t) {
+            const rsrc_t rw = make_rsrc(wsrc, t < n_stages && wvalid ? 0x7fffffffu : 0u);
+            load_w<B, GQ, HZ>(wr[0], rw, t >> 1, 2 * (t & 1), lane);
+            load_w<B, GQ, HZ>(wr[1], rw, t >> 1, 2 * (t & 1) + 1, lane);
+            load_x(xr, make_rsrc(xsrc, t < n_stages ? xbytes : 0u), xvoff, xcol, a.K, t * kStageK);
         };
-        auto mfma_step = [&](int j) {
+        auto to_lds = [&](uint8_t* stage) {
+            store_x(xr, stage + xdst);
+            dequant_to_lds<B, HZ>(wr[0], stage + wdst);
+            dequant_to_lds<B, HZ>(wr[1], stage + wdst + 64);
+        };
+        load_stage(0);
+        to_lds(smem);
+        load_stage(1);
+        __syncthreads();
+        for (int s = 0; s < n_stages; ++s) {
+            // stage s+1: registers -> LDS (the buffer the consumers are not reading); stage s+2: global -> registers
+            to_lds(smem + (kStageBytes - (s & 1) * kStageBytes));
+            load_stage(s + 2);
+            __syncthreads();
+        }
+    } else {
+        // ---------------------------------------------------------------- consumer
+        // MFMA operand addresses: lanes with h = 0 / 1 take the two 8-column groups of a 16-column step
+        const int wfrag = (wm * 128 + r) * kRowBytes + h * 16;
+        const int xfrag = kWTile + (wn * 64 + r) * kRowBytes + h * 16;
+        __syncthreads();
+        for (int s = 0; s < n_stages; ++s) {
+            const uint8_t* cur = smem + (s & 1) * kStageBytes;
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+            for (int j = 0; j < 4; ++j) {
+                half8_t wf[4], xf[2];
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+                    wf[mb] = *reinterpret_cast<const half8_t*>(cur + wfrag + mb * 32 * kRowBytes + j * 32);
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb)
-                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[j & 1][mb], xf[j & 1][nb], acc[mb][nb], 0, 0, 0);
-        };
-        // One stage: the four 16-column MFMA steps of stage s alternate with the pieces of the work for
-        // later stages (stage s+1: registers -> fp16 -> the other LDS buffer; stage s+2: global ->
-        // registers).  The fences keep this order: a wave cannot overlap its own phases otherwise, and
-        // with short alternating pieces the two waves of a SIMD keep both the matrix and the vector pipe fed.
-        Dequant<B, HZ> dq;
-        read_frags(0);
-        store_x(xr, nxt + xdst);
-        load_stage_x(s + 2);
-        dq.start(wr);
-        load_stage_w(s + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(1);
-        mfma_step(0);
-        __builtin_amdgcn_sched_barrier(0);
-        dq.insert();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(2);
-        mfma_step(1);
-        __builtin_amdgcn_sched_barrier(0);
-        dq.emit(0, nxt + wdst);
-        dq.emit(1, nxt + wdst);
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(3);
-        mfma_step(2);
-        __builtin_amdgcn_sched_barrier(0);
-        dq.emit(2, nxt + wdst);
-        dq.emit(3, nxt + wdst);
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_step(3);
-        __syncthreads();
+                    xf[nb] = *reinterpret_cast<const half8_t*>(cur + xfrag + nb * 32 * kRowBytes + j * 32);
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb)
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[mb], xf[nb], acc[mb][nb], 0, 0, 0);
+            }
+            __syncthreads();
+        }
     }
 
     // epilogue: accumulators -> fp16 -> LDS as [token][row] -> coalesced 16-byte stores
     // C[i][j] of a 32x32 block: i = row (8 * (v / 4) + 4 * h + v % 4), j = token (lane % 32)
     constexpr int kOutRow = kTM * 2 + 16;  // bytes per token row of the output tile in LDS
     uint8_t* otile = smem;                 // 256 * 528 = 135,168 bytes, the stage buffers are free now
+    if (wave < kConsumerWaves)
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -350,7 +338,7 @@ __global__ void __launch_bounds__(512, 1) mpgemm_kernel(GemmArgs a) {
     __syncthreads();
     const int m0 = blockIdx.x * kTM;
     const bool fast = (a.M % 8 == 0);  // 16-byte aligned rows of y
-    for (int piece = tid; piece < kTN * (kTM / 8); piece += 512) {
+    for (int piece = tid; piece < kTN * (kTM / 8); piece += kThreads) {
         const int n = piece / (kTM / 8), c8 = piece % (kTM / 8);
         const int gn = n0 + n, gm = m0 + c8 * 8;
         if (gn >= a.N || gm >= a.M) continue;
@@ -376,7 +364,7 @@ static int launch_cfg(const GemmArgs& a, hipStream_t st) {
         attr_set = true;
     }
     dim3 grid((unsigned)((a.M + kTM - 1) / kTM), (unsigned)((a.N + kTN - 1) / kTN));
-    hipLaunchKernelGGL((mpgemm_kernel<B, GQ, HZ>), grid, dim3(512), kGemmLdsBytes, st, a);
+    hipLaunchKernelGGL((mpgemm_kernel<B, GQ, HZ>), grid, dim3(kThreads), kGemmLdsBytes, st, a);
     return launch_status();
 }
 
