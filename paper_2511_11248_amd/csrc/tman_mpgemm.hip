@@ -15,9 +15,10 @@
 //            with the per-block constants (scale, -(1024 + zero) * scale) computed once per block.
 //            A lookup per weight in LDS would compete with the MFMA operand reads for LDS bandwidth.
 // The fp16 weight tile goes to LDS and is shared by the waves of the workgroup (each weight is
-// dequantized once per 256 tokens); activations are staged next to it unchanged.  Pipeline (the GPU form of DMA -> vector -> matrix): global loads of stage s+2 are in
-// flight while stage s+1 is dequantized into the other LDS buffer and stage s feeds
-// v_mfma_f32_32x32x16_f16 (fp32 accumulation); one barrier per stage.
+// dequantized once per 256 tokens); activations are staged next to it unchanged.  Pipeline (the GPU
+// form of DMA -> vector -> matrix): producer waves keep global loads two stages ahead in registers and
+// write fp16 stages into a ring of four LDS buffers; consumer waves feed v_mfma_f32_32x32x16_f16
+// (fp32 accumulation) from the ring; one barrier per 32-column stage.
 #include <hip/hip_fp16.h>
 
 #include "tman_internal.h"
@@ -30,20 +31,31 @@ typedef float float16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kTM = 256;      // rows of W (output features) per workgroup
 constexpr int kTN = 256;      // tokens per workgroup
-constexpr int kStageK = 64;   // columns per pipeline stage (half a tile block)
-constexpr int kRowBytes = kStageK * 2 + 16;  // padded LDS row: 36 dwords, conflict-free 16-byte accesses
-constexpr int kWTile = kTM * kRowBytes;
-constexpr int kXTile = kTN * kRowBytes;
-constexpr int kStageBytes = kWTile + kXTile;
-constexpr int kGemmLdsBytes = 2 * kStageBytes;  // double buffered: 147,456 of the CU's 160 KB
+constexpr int kStageK = 32;   // columns per pipeline stage (one 32-weight block of the layout)
+constexpr int kRowBytes = kStageK * 2 + 16;  // padded LDS row: 20 dwords, conflict-free 16-byte accesses
+constexpr int kRing = 4;      // stage buffers in LDS
+constexpr int kSets = 4;      // register sets of the producers = stages of global loads in flight
+constexpr int kXcds = 8;      // workgroups are dealt to the chip's 8 XCDs (one L2 each) round robin
+
+// A workgroup covers RB row blocks (64 * RB output features) x 256 tokens; RB = 2, 3 or 4 is chosen
+// per call so that the number of workgroups fills the compute units best.
+template <int RB>
+struct Tile {
+    static constexpr int TM = RB * 64;
+    static constexpr int WBytes = TM * kRowBytes;    // fp16 weights of a stage, padded rows
+    static constexpr int XBytes = kTN * kStageK * 2; // activations of a stage, 64-byte rows, chunks swizzled
+    static constexpr int StageBytes = WBytes + XBytes;
+    static constexpr int OutRow = TM * 2 + 16;       // bytes per token of the output tile in LDS
+    static constexpr int LdsBytes = kRing * StageBytes > kTN * OutRow ? kRing * StageBytes : kTN * OutRow;
+};
 
 struct GemmArgs {
     const uint8_t* tiles;
     const _Float16* x;
     _Float16* y;
     int M, N, K, n_row_blocks, n_ktiles;
+    int m_tiles, n_tiles;
 };
 
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
@@ -194,52 +206,52 @@ __device__ __forceinline__ void dequant_to_lds(const WRegs<B>& r, uint8_t* wrow)
     for (int q = 0; q < 4; ++q) dq.emit(q, wrow);
 }
 
-// activation staging: plain 16-byte pieces (8 columns of one token), eight per producer thread and
-// stage; eight consecutive lanes cover the 128 bytes of one token row
-constexpr int kXPieces = 8;
-struct XRegs {
-    u32x4 p[kXPieces];
-};
-constexpr int kXPieceStride = 32 * kRowBytes;  // pieces i and i + 1 of a thread are 32 tokens apart
-constexpr uint32_t kOutOfRange = 0x80000000u;
+// Activation staging: the 64 bytes a token contributes to a stage are four 16-byte chunks.  They go
+// from global memory straight into LDS (no registers, no LDS store instruction); such a load writes
+// the 64 lanes' 16 bytes consecutively, i.e. 16 token rows of 64 bytes per wave instruction.  Rows are
+// not padded, so chunk c of token row R is kept at position c ^ ((R >> 2) & 3) of its row: the MFMA
+// operand reads of 16 consecutive rows then fall into 16 different 16-byte bank groups.  The
+// permutation is applied on the global-address side, where every lane is free to pick its source.
+constexpr int kXLoads = 4;  // wave instructions per producer wave and stage (16 in all)
 
-// `rx` covers the workgroup's token rows from their first column (or nothing); rows beyond N lie
-// past its end.  k0: first column of the stage, col: first column of the thread's piece in the stage.
-__device__ __forceinline__ void load_x(XRegs& r, rsrc_t rx, const uint32_t (&voff)[kXPieces], int col, int K, int k0) {
-    const bool inside = col + 8 <= K - k0;  // K is a multiple of 32, so pieces are all-or-nothing
-#pragma unroll
-    for (int i = 0; i < kXPieces; ++i)
-        r.p[i] = __builtin_amdgcn_raw_buffer_load_b128(rx, inside ? voff[i] : kOutOfRange, k0 * 2, 0);
-}
-
-__device__ __forceinline__ void store_x(const XRegs& r, uint8_t* dst) {
-#pragma unroll
-    for (int i = 0; i < kXPieces; ++i) *reinterpret_cast<u32x4*>(dst + i * kXPieceStride) = r.p[i];
-}
-
-// Workgroup = 12 waves, three per SIMD.  Waves 0..7 are consumers: wave (wm, wn) owns 128 rows x 64
-// tokens of the 256 x 256 tile and does nothing but read MFMA operands from LDS and issue MFMAs.
-// Waves 8..11 are producers: wave p turns row block p of each stage into fp16 in LDS and stages a
-// quarter of the activations.  Vector work of the producers and matrix work of the consumers come
-// from different waves of a SIMD, so the hardware overlaps them without any help from the schedule.
+// Workgroup = 12 waves, three per SIMD.  Waves 0..7 are consumers: wave (wm, wn) owns 32 RB rows x 64
+// tokens of the tile and does nothing but read MFMA operands from LDS and issue MFMAs.  Waves 8..11
+// are producers: wave p < RB turns row block p of each stage into fp16 in LDS, and all four stage the
+// activations.  Vector work of the producers and matrix work of the consumers come from different
+// waves of a SIMD, so the hardware overlaps them without any help from the instruction schedule.
+//
+// Ring protocol, one barrier at the end of every stage s: before it the producers have written stage
+// s+2 and the consumers have finished reading stage s.  Hence consumers may prefetch operands of stage
+// s+1 during stage s, and the buffer written during stage s (stage s+2) was last read in stage s-2.
+// The producers hold the global loads of four further stages in registers: at the rates of this kernel
+// that many bytes in flight are needed to cover the latency of HBM and L2.
 constexpr int kConsumerWaves = 8;
 constexpr int kThreads = 768;
 
-template <int B, int GQ, bool HZ>
+template <int B, int GQ, bool HZ, int RB>
 __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
+    using T = Tile<RB>;
     constexpr int MSZ = HZ ? 4 : 2;
     constexpr int TB = B * 1024 + 64 * (kKTile / GQ) * MSZ;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
+    // Tile of this workgroup.  Consecutive workgroup ids go to consecutive XCDs; the n_tiles workgroups
+    // that share the weights of one row tile get ids that are 8 apart, i.e. the same XCD and L2.
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int mt = (slot / a.n_tiles) * kXcds + xcd, nt = slot % a.n_tiles;
+    if (mt >= a.m_tiles) return;
+
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int n0 = blockIdx.y * kTN;
-    const int n_stages = (a.K + kStageK - 1) / kStageK;
+    const int n0 = nt * kTN;
+    // K is a multiple of the quantization group, hence of 32.  The loops run a multiple of four stages
+    // (no conditional code between the loads and their use); a stage beyond K holds zero activations.
+    const int k_stages = a.K / kStageK, n_stages = (k_stages + kSets - 1) & ~(kSets - 1);
 
-    float16_t acc[4][2];
+    float16_t acc[RB][2];
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
@@ -248,101 +260,160 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
 
     if (wave >= kConsumerWaves) {
         // ---------------------------------------------------------------- producer
-        const int p = wave - kConsumerWaves, ptid = tid - kConsumerWaves * 64;
-        const int rbw = blockIdx.x * 4 + p;
-        const bool wvalid = rbw < a.n_row_blocks;
+        const int p = wave - kConsumerWaves;
+        const int rbw = mt * RB + p;
+        // the producers' short vector bursts gate every stage: issue them ahead of the consumers' MFMAs
+        __builtin_amdgcn_s_setprio(3);
+        const bool wvalid = p < RB && rbw < a.n_row_blocks;
         const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? rbw : 0) * a.n_ktiles * TB;
         const int xrows = a.N - n0 < kTN ? a.N - n0 : kTN;
         const _Float16* xsrc = a.x + (size_t)n0 * a.K;
         const uint32_t xbytes = (uint32_t)xrows * (uint32_t)a.K * 2u;
-        const int xcol = (ptid & 7) * 8;
-        uint32_t xvoff[kXPieces];
+        // wave instruction i of this wave fills token rows 16 (4p + i) .. + 15; lane = 4 * row + position
+        uint32_t xvoff[kXLoads];
 #pragma unroll
-        for (int i = 0; i < kXPieces; ++i)
-            xvoff[i] = ((uint32_t)((ptid >> 3) + 32 * i) * (uint32_t)a.K + (uint32_t)xcol) * 2u;
-        const int xdst = kWTile + (ptid >> 3) * kRowBytes + (ptid & 7) * 16;
-        const int wdst = (p * 64 + lane) * kRowBytes;  // this lane's 128 bytes in the weight tile
-
-        WRegs<B> wr[2];
-        XRegs xr;
-        // stage t: global -> registers; a stage beyond K reads zeros
-        auto load_stage = [&](int t) {
-            const rsrc_t rw = make_rsrc(wsrc, t < n_stages && wvalid ? 0x7fffffffu : 0u);
-            load_w<B, GQ, HZ>(wr[0], rw, t >> 1, 2 * (t & 1), lane);
-            load_w<B, GQ, HZ>(wr[1], rw, t >> 1, 2 * (t & 1) + 1, lane);
-            load_x(xr, make_rsrc(xsrc, t < n_stages ? xbytes : 0u), xvoff, xcol, a.K, t * kStageK);
-        };
-        auto to_lds = [&](uint8_t* stage) {
-            store_x(xr, stage + xdst);
-            dequant_to_lds<B, HZ>(wr[0], stage + wdst);
-            dequant_to_lds<B, HZ>(wr[1], stage + wdst + 64);
-        };
-        load_stage(0);
-        to_lds(smem);
-        load_stage(1);
-        __syncthreads();
-        for (int s = 0; s < n_stages; ++s) {
-            // stage s+1: registers -> LDS (the buffer the consumers are not reading); stage s+2: global -> registers
-            to_lds(smem + (kStageBytes - (s & 1) * kStageBytes));
-            load_stage(s + 2);
-            __syncthreads();
+        for (int i = 0; i < kXLoads; ++i) {
+            const uint32_t row = 16u * (4u * p + i) + (lane >> 2), chunk = (lane & 3) ^ ((lane >> 4) & 3);
+            xvoff[i] = (row * (uint32_t)a.K + chunk * 8u) * 2u;
         }
+        const int xdst = T::WBytes + p * kXLoads * 1024;
+        const int wdst = (p * 64 + lane) * kRowBytes;  // this lane's 64 bytes in the weight tile
+
+        WRegs<B> wr[kSets];
+        // stage t: activations global -> ring.  Rows beyond N and stages beyond K are out of the buffer's
+        // range; whatever LDS holds for them only reaches outputs that are never stored, or is skipped.
+        auto load_x = [&](int t) {
+            const rsrc_t rx = make_rsrc(xsrc, t < k_stages ? xbytes : 0u);
+            uint8_t* dst = smem + (t & (kRing - 1)) * T::StageBytes + xdst;
+#pragma unroll
+            for (int i = 0; i < kXLoads; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(dst + i * 1024), 16,
+                                                         xvoff[i], t * kStageK * 2, 0, 0);
+        };
+        // stage t: packed weights global -> register set (all four waves issue the same number of loads,
+        // so that one count of outstanding loads fits all; a wave without a row block reads nothing)
+        auto load_wregs = [&](int set, int t) {
+            load_w<B, GQ, HZ>(wr[set], make_rsrc(wsrc, t < k_stages && wvalid ? 0x7fffffffu : 0u), t >> 2, t & 3, lane);
+        };
+        auto w_to_lds = [&](int set, int t) {
+            if (p < RB) dequant_to_lds<B, HZ>(wr[set], smem + (t & (kRing - 1)) * T::StageBytes + wdst);
+        };
+        // prologue: stages 0 and 1 complete in the ring, activations of stage 2 on their way, weights of
+        // stages 2..5 in the register sets 2, 3, 0, 1
+        load_x(0);
+        load_x(1);
+        load_wregs(0, 0);
+        load_wregs(1, 1);
+        load_wregs(2, 2);
+        load_wregs(3, 3);
+        w_to_lds(0, 0);
+        w_to_lds(1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");  // all but the weights of stages 2 and 3 (two loads each)
+        load_x(2);
+        load_wregs(0, 4);
+        load_wregs(1, 5);
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        // During stage s: activations of stage s+3 -> ring (that buffer was last read in stage s-1),
+        // weights of stage s+2 registers -> ring, weights of stage s+6 global -> the same registers.
+        // Loads complete in order.  Before the barrier the activations of stage s+2 must have landed;
+        // they were issued first in stage s-1, so 8 loads are younger: 2 weight loads of stage s-1, 4
+        // activation loads and 2 weight loads of stage s.
+        for (int s = 0; s < n_stages; s += kSets) {
+#pragma unroll
+            for (int u = 0; u < kSets; ++u) {
+                load_x(s + u + 3);
+                __builtin_amdgcn_sched_barrier(0);
+                w_to_lds((u + 2) % kSets, s + u + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                load_wregs((u + 2) % kSets, s + u + 6);
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            }
+        }
+        // loads of stages past the end may still be on their way to LDS, which the epilogue reuses
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     } else {
         // ---------------------------------------------------------------- consumer
         // MFMA operand addresses: lanes with h = 0 / 1 take the two 8-column groups of a 16-column step
-        const int wfrag = (wm * 128 + r) * kRowBytes + h * 16;
-        const int xfrag = kWTile + (wn * 64 + r) * kRowBytes + h * 16;
+        const int wfrag = (wm * RB * 32 + r) * kRowBytes + h * 16;
+        // activation operand: token row wn * 64 + nb * 32 + r, chunk 2j + h, kept at chunk ^ ((r >> 2) & 3)
+        const int xrow = T::WBytes + (wn * 64 + r) * (kStageK * 2);
+        const int xchunk[2] = {xrow + ((h ^ ((r >> 2) & 3)) * 16), xrow + (((2 + h) ^ ((r >> 2) & 3)) * 16)};
+        // Operand registers: one weight operand per 32-row block, reloaded for the next 16-column step
+        // as soon as its two MFMAs are issued (so the read has the other blocks' MFMAs to land), and two
+        // pairs of activation operands (this step's and the next one's).
+        half8_t wf[RB], xf[2][2];
+        auto read_w = [&](int mb, const uint8_t* stage, int j) {
+            wf[mb] = *reinterpret_cast<const half8_t*>(stage + wfrag + mb * 32 * kRowBytes + j * 32);
+        };
+        auto read_x = [&](int set, const uint8_t* stage, int j) {
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb)
+                xf[set][nb] = *reinterpret_cast<const half8_t*>(stage + xchunk[j] + nb * 32 * (kStageK * 2));
+        };
         __syncthreads();
-        for (int s = 0; s < n_stages; ++s) {
-            const uint8_t* cur = smem + (s & 1) * kStageBytes;
+        read_x(0, smem, 0);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                half8_t wf[4], xf[2];
+        for (int mb = 0; mb < RB; ++mb) read_w(mb, smem, 0);
+        for (int s = 0; s < k_stages; ++s) {
+            const uint8_t* cur = smem + (s & (kRing - 1)) * T::StageBytes;
+            const uint8_t* nxt = smem + ((s + 1) & (kRing - 1)) * T::StageBytes;
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-                    wf[mb] = *reinterpret_cast<const half8_t*>(cur + wfrag + mb * 32 * kRowBytes + j * 32);
+            for (int j = 0; j < 2; ++j) {
+                // operands after this step: step 1 of this stage, or step 0 of stage s+1, which is complete
+                // in the ring (past the last stage this reads stale LDS that is never used)
+                const uint8_t* ahead = j == 0 ? cur : nxt;
+                read_x(j ^ 1, ahead, j ^ 1);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int nb = 0; nb < 2; ++nb)
-                    xf[nb] = *reinterpret_cast<const half8_t*>(cur + xfrag + nb * 32 * kRowBytes + j * 32);
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
+                for (int mb = 0; mb < RB; ++mb) {
 #pragma unroll
                     for (int nb = 0; nb < 2; ++nb)
-                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[mb], xf[nb], acc[mb][nb], 0, 0, 0);
+                        acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[mb], xf[j][nb], acc[mb][nb], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    read_w(mb, ahead, j ^ 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            __syncthreads();
+            // Plain barrier: this wave has no LDS writes to publish, and its outstanding reads (stage
+            // s+1) need not land before it; everything it read from stage s has been consumed.
+            asm volatile("s_barrier" ::: "memory");
         }
+        // the producers run a multiple of four stages; meet them at the barriers of the padding stages
+        for (int s = k_stages; s < n_stages; ++s) asm volatile("s_barrier" ::: "memory");
     }
 
     // epilogue: accumulators -> fp16 -> LDS as [token][row] -> coalesced 16-byte stores
     // C[i][j] of a 32x32 block: i = row (8 * (v / 4) + 4 * h + v % 4), j = token (lane % 32)
-    constexpr int kOutRow = kTM * 2 + 16;  // bytes per token row of the output tile in LDS
-    uint8_t* otile = smem;                 // 256 * 528 = 135,168 bytes, the stage buffers are free now
-    if (wave < kConsumerWaves)
+    uint8_t* otile = smem;  // the stage buffers are free now
+    if (wave < kConsumerWaves) {
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+        for (int mb = 0; mb < RB; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-            uint8_t* col = otile + (wn * 64 + nb * 32 + r) * kOutRow + (wm * 128 + mb * 32 + 4 * h) * 2;
+            for (int nb = 0; nb < 2; ++nb) {
+                uint8_t* col = otile + (wn * 64 + nb * 32 + r) * T::OutRow + ((wm * RB + mb) * 32 + 4 * h) * 2;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                half2_t lo, hi;
-                lo.x = (_Float16)acc[mb][nb][4 * g + 0];
-                lo.y = (_Float16)acc[mb][nb][4 * g + 1];
-                hi.x = (_Float16)acc[mb][nb][4 * g + 2];
-                hi.y = (_Float16)acc[mb][nb][4 * g + 3];
-                u32x2 w = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
-                *reinterpret_cast<u32x2*>(col + g * 16) = w;  // rows 8g + 4h + 0..3
+                for (int g = 0; g < 4; ++g) {
+                    half2_t lo, hi;
+                    lo.x = (_Float16)acc[mb][nb][4 * g + 0];
+                    lo.y = (_Float16)acc[mb][nb][4 * g + 1];
+                    hi.x = (_Float16)acc[mb][nb][4 * g + 2];
+                    hi.y = (_Float16)acc[mb][nb][4 * g + 3];
+                    u32x2 w = {__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)};
+                    *reinterpret_cast<u32x2*>(col + g * 16) = w;  // rows 8g + 4h + 0..3
+                }
             }
-        }
+    }
     __syncthreads();
-    const int m0 = blockIdx.x * kTM;
+    const int m0 = mt * T::TM;
     const bool fast = (a.M % 8 == 0);  // 16-byte aligned rows of y
-    for (int piece = tid; piece < kTN * (kTM / 8); piece += kThreads) {
-        const int n = piece / (kTM / 8), c8 = piece % (kTM / 8);
+    for (int piece = tid; piece < kTN * (T::TM / 8); piece += kThreads) {
+        const int n = piece / (T::TM / 8), c8 = piece % (T::TM / 8);
         const int gn = n0 + n, gm = m0 + c8 * 8;
         if (gn >= a.N || gm >= a.M) continue;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(otile + n * kOutRow + c8 * 16);
+        const u32x4 v = *reinterpret_cast<const u32x4*>(otile + n * T::OutRow + c8 * 16);
         _Float16* dst = a.y + (size_t)gn * a.M + gm;
         if (fast && gm + 8 <= a.M) {
             *reinterpret_cast<u32x4*>(dst) = v;
@@ -354,18 +425,56 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
     }
 }
 
-template <int B, int GQ, bool HZ>
-static int launch_cfg(const GemmArgs& a, hipStream_t st) {
+template <int B, int GQ, bool HZ, int RB>
+static int launch_tile(GemmArgs a, hipStream_t st) {
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&mpgemm_kernel<B, GQ, HZ>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLdsBytes) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&mpgemm_kernel<B, GQ, HZ, RB>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, Tile<RB>::LdsBytes) != hipSuccess)
             return TMAN_ERR_LAUNCH;
         attr_set = true;
     }
-    dim3 grid((unsigned)((a.M + kTM - 1) / kTM), (unsigned)((a.N + kTN - 1) / kTN));
-    hipLaunchKernelGGL((mpgemm_kernel<B, GQ, HZ>), grid, dim3(kThreads), kGemmLdsBytes, st, a);
+    a.m_tiles = (a.n_row_blocks + RB - 1) / RB;
+    a.n_tiles = (a.N + kTN - 1) / kTN;
+    const unsigned grid = (unsigned)((a.m_tiles + kXcds - 1) / kXcds * kXcds * a.n_tiles);
+    hipLaunchKernelGGL((mpgemm_kernel<B, GQ, HZ, RB>), dim3(grid), dim3(kThreads), Tile<RB>::LdsBytes, st, a);
     return launch_status();
+}
+
+// Rows per workgroup: the choice that needs the least time, counted as rounds of workgroups over the
+// compute units times rows per workgroup, with a small bonus for larger tiles (fewer operand reads
+// and less dequantization per MFMA).
+static int choose_row_blocks(int n_row_blocks, int N) {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            n_cu = prop.multiProcessorCount;
+        if (n_cu <= 0) n_cu = 256;
+    }
+    const int n_tiles = (N + kTN - 1) / kTN;
+    const double penalty[5] = {0, 0, 1.10, 1.03, 1.0};
+    int best = 4;
+    double best_cost = 1e30;
+    for (int rb = 4; rb >= 2; --rb) {
+        const long long wgs = (long long)((n_row_blocks + rb - 1) / rb) * n_tiles;
+        const double cost = (double)((wgs + n_cu - 1) / n_cu) * rb * penalty[rb];
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = rb;
+        }
+    }
+    return best;
+}
+
+template <int B, int GQ, bool HZ>
+static int launch_cfg(const GemmArgs& a, hipStream_t st) {
+    switch (choose_row_blocks(a.n_row_blocks, a.N)) {
+        case 2: return launch_tile<B, GQ, HZ, 2>(a, st);
+        case 3: return launch_tile<B, GQ, HZ, 3>(a, st);
+        default: return launch_tile<B, GQ, HZ, 4>(a, st);
+    }
 }
 
 template <int B, bool HZ>
@@ -389,6 +498,7 @@ int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, voi
     a.K = L.K;
     a.n_row_blocks = L.n_row_blocks;
     a.n_ktiles = L.n_ktiles;
+    a.m_tiles = a.n_tiles = 0;
     if (L.bits == 1) return L.has_zero ? launch_group<1, true>(L.group, a, st) : launch_group<1, false>(L.group, a, st);
     if (L.bits == 2) return launch_group<2, true>(L.group, a, st);
     return launch_group<4, true>(L.group, a, st);
