@@ -125,3 +125,59 @@ def test_status_strings(lib):
     with pytest.raises(tman.TmanError) as e:
         api._check(-3, "here")
     assert "group" in str(e.value)
+
+
+def _ptrs(*vals):
+    return (C.c_void_p * len(vals))(*vals)
+
+
+def test_batched_lut_build_rejects_bad_arguments(lib):
+    x, lut, K = _ptrs(FAKE, FAKE), _ptrs(FAKE, FAKE), (C.c_int32 * 2)(256, 512)
+    assert lib.tman_build_lut_batch(2, None, 1, K, 64, lut, None) == -1
+    assert lib.tman_build_lut_batch(2, x, 1, None, 64, lut, None) == -1
+    assert lib.tman_build_lut_batch(2, x, 1, K, 64, None, None) == -1
+    assert lib.tman_build_lut_batch(2, x, 1, K, 48, lut, None) == -3
+    assert lib.tman_build_lut_batch(0, x, 1, K, 64, lut, None) == -4
+    assert lib.tman_build_lut_batch(257, x, 1, K, 64, lut, None) == -4
+    assert lib.tman_build_lut_batch(2, x, 0, K, 64, lut, None) == -4
+    assert lib.tman_build_lut_batch(2, x, 9, K, 64, lut, None) == -4
+    assert lib.tman_build_lut_batch(2, _ptrs(FAKE, None), 1, K, 64, lut, None) == -1
+    assert lib.tman_build_lut_batch(2, x, 1, K, 64, _ptrs(FAKE, None), None) == -1
+    assert lib.tman_build_lut_batch(2, x, 1, (C.c_int32 * 2)(256, 500), 64, lut, None) == -4
+    assert lib.tman_build_lut_batch(2, x, 1, (C.c_int32 * 2)(256, 0), 64, lut, None) == -4
+    assert lib.tman_build_lut_batch(2, x, 1, K, 64, _ptrs(FAKE, FAKE + 8), None) == -6
+
+
+def test_batched_gemv_rejects_bad_arguments(lib):
+    shapes = (api._CShape * 2)(_shape(M=64, K=256), _shape(M=128, K=512))
+    packed, lut, y = _ptrs(FAKE, FAKE), _ptrs(FAKE, FAKE), _ptrs(FAKE, FAKE)
+    ws = _ptrs(FAKE, FAKE + 0x10000)
+    need = [lib.tman_mpgemv_workspace_bytes(C.byref(shapes[i]), 1) for i in range(2)]
+    wsb = (C.c_size_t * 2)(*need)
+    assert lib.tman_mpgemv_batch_desc_bytes(2) >= 2 * 64 and lib.tman_mpgemv_batch_desc_bytes(2) % 16 == 0
+    assert lib.tman_mpgemv_batch_desc_bytes(0) == 0 and lib.tman_mpgemv_batch_desc_bytes(257) == 0
+
+    def prepare(count=2, shapes=shapes, packed=packed, lut=lut, N=1, y=y, ws=ws, wsb=wsb, desc=FAKE):
+        return lib.tman_mpgemv_batch_prepare(count, shapes, packed, lut, N, y, ws, wsb, desc, None)
+
+    assert prepare(shapes=None) == -1
+    assert prepare(count=0) == -4 and prepare(count=257) == -4
+    assert prepare(N=0) == -4 and prepare(N=9) == -4
+    assert prepare(packed=None) == -1 and prepare(lut=None) == -1 and prepare(y=None) == -1
+    assert prepare(ws=None) == -1 and prepare(wsb=None) == -1 and prepare(desc=None) == -1
+    assert prepare(desc=FAKE + 4) == -6
+    assert prepare(packed=_ptrs(FAKE, None)) == -1
+    assert prepare(lut=_ptrs(FAKE, FAKE + 2)) == -6
+    assert prepare(wsb=(C.c_size_t * 2)(need[0], need[1] - 1)) == -5
+    assert prepare(ws=_ptrs(FAKE, FAKE)) == -5  # two GEMVs of a launch may not share a workspace
+    mixed = (api._CShape * 2)(_shape(M=64, K=256, bits=4), _shape(M=128, K=512, bits=2))
+    assert prepare(shapes=mixed) == -4  # one launch runs one weight format
+    bad = (api._CShape * 2)(_shape(M=64, K=256), _shape(M=128, K=500))
+    assert prepare(shapes=bad) == -4
+
+    assert lib.tman_mpgemv_batch_run(2, None, 1, FAKE, None) == -1
+    assert lib.tman_mpgemv_batch_run(2, shapes, 1, None, None) == -1
+    assert lib.tman_mpgemv_batch_run(2, shapes, 1, FAKE + 8, None) == -6
+    assert lib.tman_mpgemv_batch_run(0, shapes, 1, FAKE, None) == -4
+    assert lib.tman_mpgemv_batch_run(2, shapes, 9, FAKE, None) == -4
+    assert lib.tman_mpgemv_batch_run(2, mixed, 1, FAKE, None) == -4
