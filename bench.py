@@ -27,6 +27,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per launch of the dominant kernels on the default workloads, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script scaled by a plain copy of known size (--calibration-copy); the counters
+# cannot be read from inside the process.  Source: profiles/mpgemv_7b_w2g64_hbm_traffic.txt.
+MEASURED_TRAFFIC_BYTES = {
+    ("mpgemv", "7b_w2g64", 1): 64_947_200 + 142_336,
+    ("mpgemm", "prefill_w4g64", 1024): 92_633_088 + 22_544_384,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -39,6 +47,9 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device-to-device copy of 256 MiB before the timed region: under "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its known traffic calibrates the counters")
     return ap.parse_args()
 
 
@@ -115,6 +126,14 @@ def main():
             e1.record()
             events.append((e0, e1))
 
+    if args.calibration_copy:
+        src = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i, False)
     torch.cuda.synchronize()
@@ -135,7 +154,7 @@ def main():
     achieved = bytes_per_launch / avg_launch_s / 1e9
     roofline = {
         "bound": "hbm", "kernel": "mpgemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(("mpgemv", w.name, N)),
         "launches": n_launch, "avg_launch_us": round(avg_launch_s * 1e6, 3),
         "median_launch_us": round(gemv_ms[n_launch // 2] * 1e3, 3),
         "algorithmic_bytes_per_launch": int(bytes_per_launch),
@@ -184,7 +203,7 @@ def main():
             "ms_per_call": round(avg_ms, 4), "min_ms": round(ts[0], 4),
             "roofline": {"bound": "mfma", "kernel": "mpgemm_kernel", "achieved": round(tf, 1),
                          "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / MFMA_F16_PEAK_TFLOPS, 4),
-                         "traffic": None},
+                         "traffic": MEASURED_TRAFFIC_BYTES.get(("mpgemm", pw.name, NP))},
         }
         del pblob, px, py
 
