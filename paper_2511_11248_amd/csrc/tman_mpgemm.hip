@@ -2,7 +2,7 @@
 // (Sec. 4.1 "Unified Layout through Fused LUT-based Dequantization", Sec. 4.2 three-stage pipeline).
 //
 // The weights stay in the bit-serial layout decoding uses (lane = row, 64 rows x 128 columns per tile
-// block).  Per 64-column stage a wave turns the bit-plane words of its 64 rows into fp16 weights:
+// block).  Per 32-column stage a producer wave turns the bit-plane words of its 64 rows into fp16 weights:
 //   level 1  bit-serial -> bit-parallel (Sec. 4.1 "Bit repacking"): two rounds of bit-field inserts
 //            transpose a 4 x 32 bit matrix in 16 ALU ops, giving for each 32-weight block four words
 //            of eight 4-bit codes, word o holding the codes of weights 4f + o;
@@ -15,9 +15,9 @@
 //            with the per-block constants (scale, -(1024 + zero) * scale) computed once per block.
 //            A lookup per weight in LDS would compete with the MFMA operand reads for LDS bandwidth.
 // The fp16 weight tile goes to LDS and is shared by the waves of the workgroup (each weight is
-// dequantized once per 256 tokens); activations are staged next to it unchanged.  Pipeline (the GPU
-// form of DMA -> vector -> matrix): producer waves keep global loads two stages ahead in registers and
-// write fp16 stages into a ring of four LDS buffers; consumer waves feed v_mfma_f32_32x32x16_f16
+// dequantized once per 256 tokens); activations go from global memory straight into LDS.  Pipeline (the
+// GPU form of DMA -> vector -> matrix): producer waves keep packed weights four stages ahead in registers
+// and fill a ring of four LDS stage buffers; consumer waves feed v_mfma_f32_32x32x16_f16
 // (fp32 accumulation) from the ring; one barrier per 32-column stage.
 #include <hip/hip_fp16.h>
 
