@@ -44,9 +44,9 @@ def test_tables_and_group_sums(oracle_lib, N, K, group):
     # padding (tokens beyond N, columns beyond K) is zero
     NP = 1 if N == 1 else 2 if N == 2 else 4 if N <= 4 else 8
     nkt = -(-K // 128)
-    allT = raw[: nkt * 1024 * NP].view(np.float16).reshape(nkt * 32, 16, NP)
-    assert np.all(allT[:, :, N:] == 0)
-    assert np.all(allT[K // 4:, :, :] == 0)
+    allT, _ = oracle.lut_layout_decode(raw, NP, nkt * 128, group)  # every padded token and column
+    assert np.all(allT[N:, :, :] == 0)
+    assert np.all(allT[:, K // 4:, :] == 0)
 
 
 def test_batched_build_matches_single_calls(oracle_lib):
