@@ -155,6 +155,13 @@ int tman_mpgemv_batch_run(int32_t count, const tman_shape_t *shapes, int32_t N, 
 int tman_mpgemm(const tman_shape_t *shape, const void *packed, const void *x, int32_t N, void *y, void *workspace,
                 size_t workspace_bytes, void *stream);
 
+/*
+ * Rows of W (output features) one workgroup of tman_mpgemm covers for this shape and N: 128, 192 or 256,
+ * chosen so that the workgroups fill the compute units of the current device best (256 units are
+ * assumed when no device is present).  Informational; 0 for an invalid shape or N < 1.
+ */
+int32_t tman_mpgemm_tile_rows(const tman_shape_t *shape, int32_t N);
+
 /* Static, human-readable name of a status code. */
 const char *tman_status_string(int status);
 

@@ -82,6 +82,8 @@ def _load():
         L.tman_mpgemv_batch_run.argtypes = [C.c_int32, sp, C.c_int32, vp, vp]
         L.tman_mpgemm.restype = C.c_int
         L.tman_mpgemm.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.tman_mpgemm_tile_rows.restype = C.c_int32
+        L.tman_mpgemm_tile_rows.argtypes = [sp, C.c_int32]
         L.tman_status_string.restype = C.c_char_p
         L.tman_status_string.argtypes = [C.c_int]
         L.tman_layout_version.restype = C.c_int32
@@ -139,6 +141,10 @@ def tman_mpgemv_workspace_bytes(shape: Shape, N: int) -> int:
 
 def tman_mpgemm_workspace_bytes(shape: Shape, N: int) -> int:
     return int(_load().tman_mpgemm_workspace_bytes(C.byref(shape.c()), N))
+
+
+def tman_mpgemm_tile_rows(shape: Shape, N: int) -> int:
+    return int(_load().tman_mpgemm_tile_rows(C.byref(shape.c()), N))
 
 
 def tman_pack_weights(shape: Shape, codes, scales, zeros, packed, stream=None) -> None:

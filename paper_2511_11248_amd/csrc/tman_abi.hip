@@ -143,6 +143,11 @@ int tman_mpgemv_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, 
                                static_cast<const GemvDesc*>(desc), count, total, (hipStream_t)stream);
 }
 
+int32_t tman_mpgemm_tile_rows(const tman_shape_t* shape, int32_t N) {
+    if (check_shape(shape) != TMAN_OK || N < 1) return 0;
+    return kRows * mpgemm_row_blocks_per_workgroup(make_layout(shape), N);
+}
+
 int tman_mpgemm(const tman_shape_t* shape, const void* packed, const void* x, int32_t N, void* y, void* workspace,
                 size_t workspace_bytes, void* stream) {
     int rc = check_shape(shape);

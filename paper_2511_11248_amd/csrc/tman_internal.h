@@ -103,5 +103,6 @@ int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc
                         long long total_tiles, hipStream_t st);
 int launch_write_descs(const GemvDesc* host, int count, GemvDesc* dev, hipStream_t st);
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);
+int mpgemm_row_blocks_per_workgroup(const Layout& L, int N);
 
 }  // namespace tman

@@ -486,6 +486,8 @@ static int launch_group(int group, const GemmArgs& a, hipStream_t st) {
     }
 }
 
+int mpgemm_row_blocks_per_workgroup(const Layout& L, int N) { return choose_row_blocks(L.n_row_blocks, N); }
+
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace,
                   hipStream_t st) {
     (void)workspace;

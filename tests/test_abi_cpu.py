@@ -181,3 +181,14 @@ def test_batched_gemv_rejects_bad_arguments(lib):
     assert lib.tman_mpgemv_batch_run(0, shapes, 1, FAKE, None) == -4
     assert lib.tman_mpgemv_batch_run(2, shapes, 9, FAKE, None) == -4
     assert lib.tman_mpgemv_batch_run(2, mixed, 1, FAKE, None) == -4
+
+
+def test_prefill_tile_rows_query(lib):
+    """The tile height follows the number of workgroups it yields (256 compute units assumed without a
+    device): small problems take the lowest tile, 768 / 1024 row blocks fill one round with 192 / 256 rows."""
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(256, 512, 4, 64, True), 128) == 128
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 1024) == 192
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(49152, 384, 4, 64, True), 200) == 192
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(65536, 384, 4, 64, True), 200) == 256
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(256, 500, 4, 64, True), 128) == 0
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(256, 512, 4, 64, True), 0) == 0

@@ -82,3 +82,20 @@ def test_full_size_prefill_sampled_tokens(oracle_lib, N):
     Y = oracle.matmul(q, s, z, x[rows], w.bits, w.group)
     err = oracle.row_relative_error(y[rows], Y)
     assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
+
+
+@pytest.mark.parametrize("M,rows", [(49152, 192), (65536, 256)])
+def test_every_tile_height(oracle_lib, M, rows):
+    """Row counts that make the launcher pick the 192- and 256-row tiles (the small cases above all run
+    with 128 rows, the benchmark shape with 192); ragged token count, K = 12 stages so the stage ring
+    wraps three times.  The oracle recomputes eight tokens in full."""
+    K, bits, group, N = 384, 4, 64, 200
+    shape = tman.Shape(M, K, bits, group, True)
+    assert tman.tman_mpgemm_tile_rows(shape, N) == rows
+    q, s, z, x = rand_case(5000 + M, M, K, N, bits, group)
+    y = mpgemm(shape, pack(shape, q, s, z), x)
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    tokens = [0, 1, 63, 64, 127, 128, 198, 199]
+    Y = oracle.matmul(q, s, z, x[tokens], bits, group)
+    err = oracle.row_relative_error(y[tokens], Y)
+    assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
