@@ -137,10 +137,13 @@ int tman_mpgemv_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, 
     if (rc != TMAN_OK) return rc;
     if (!desc) return TMAN_ERR_NULL;
     if (!aligned16(desc)) return TMAN_ERR_ALIGN;
-    long long total = 0;
-    for (int i = 0; i < count; ++i) total += plan_gemv(make_layout(&shapes[i]), N).n_workgroups;
+    int max_wg = 0;  // the launch grid is (workgroups of the largest GEMV) x count
+    for (int i = 0; i < count; ++i) {
+        const int n = plan_gemv(make_layout(&shapes[i]), N).n_workgroups;
+        if (n > max_wg) max_wg = n;
+    }
     return launch_mpgemv_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO, N,
-                               static_cast<const GemvDesc*>(desc), count, total, (hipStream_t)stream);
+                               static_cast<const GemvDesc*>(desc), count, max_wg, (hipStream_t)stream);
 }
 
 int32_t tman_mpgemm_tile_rows(const tman_shape_t* shape, int32_t N) {

@@ -100,7 +100,7 @@ int launch_build_lut_batch(int count, const void* const* x, int N, const int* K,
 int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
                   hipStream_t st);
 int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,
-                        long long total_tiles, hipStream_t st);
+                        int max_workgroups, hipStream_t st);
 int launch_write_descs(const GemvDesc* host, int count, GemvDesc* dev, hipStream_t st);
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);
 int mpgemm_row_blocks_per_workgroup(const Layout& L, int N);

@@ -331,19 +331,14 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
 #pragma unroll
     for (int i = 0; i < B; ++i) pw[i] = opaque((float)(1 << i));
 
-    // which GEMV does this workgroup belong to: binary search over the first-workgroup indices
-    int g = 0;
-    if constexpr (!SINGLE) {
-        int lo = 0, hi = a.n_gemv - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (a.descs[mid].wg_begin <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
-        }
-        g = lo;
-    }
+    // The grid is (workgroups of the largest GEMV) x (GEMVs): a workgroup knows its GEMV from its block
+    // index, without searching the descriptor table (every workgroup of a launch starts at the same time,
+    // so a chain of dependent loads here delays the whole launch); surplus workgroups leave at once.
+    const int g = SINGLE ? 0 : (int)blockIdx.y;
     const GemvDesc& d = desc_of<SINGLE>(a, g);
     const int n_seg = uniform(d.n_seg), n_ktiles = uniform(d.n_ktiles);
-    const int wg_local = (int)blockIdx.x - uniform(d.wg_begin);
+    const int wg_local = (int)blockIdx.x;
+    if (wg_local >= uniform(d.n_row_blocks) * n_seg) return;
     const int rb = wg_local / n_seg, seg = wg_local % n_seg;
     const int seg_tiles = uniform(d.seg_tiles);
     const int k0 = seg * seg_tiles;
@@ -447,7 +442,8 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
 
 template <int B, int NP, int GQ, bool HZ, bool SINGLE>
 static int launch_cfg(const KernelArgs<SINGLE>& a, int n_workgroups, hipStream_t st) {
-    hipLaunchKernelGGL((mpgemv_kernel<B, NP, GQ, HZ, SINGLE>), dim3((unsigned)n_workgroups), dim3(kWaves * 64), 0, st, a);
+    hipLaunchKernelGGL((mpgemv_kernel<B, NP, GQ, HZ, SINGLE>), dim3((unsigned)n_workgroups, (unsigned)a.n_gemv), dim3(kWaves * 64),
+                       0, st, a);
     return launch_status();
 }
 
@@ -491,12 +487,12 @@ int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, v
 }
 
 int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,
-                        long long n_workgroups, hipStream_t st) {
+                        int max_workgroups, hipStream_t st) {
     KernelArgs<false> a;
     a.single = GemvDesc{};
     a.descs = descs_dev;
     a.n_gemv = n_gemv;
-    return launch_format<false>(bits, has_zero, padded_tokens(N), group, a, (int)n_workgroups, st);
+    return launch_format<false>(bits, has_zero, padded_tokens(N), group, a, max_workgroups, st);
 }
 
 // copies up to 16 descriptors per launch from the kernel arguments into the device table
