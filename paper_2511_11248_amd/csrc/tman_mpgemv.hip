@@ -178,14 +178,25 @@ __device__ __forceinline__ float opaque(float v) {
 // the whole kernel) plus a scalar offset (the tile), so streaming costs no address arithmetic.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 constexpr int kStreamAux = 2;  // non-temporal: weights are read once, keep them from evicting the tables in L2
-__device__ __forceinline__ rsrc_t make_rsrc(const uint8_t* base) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, 0xFFFFFFFFu, 0x00020000);
+__device__ __forceinline__ rsrc_t make_rsrc(const uint8_t* base, uint32_t bytes = 0xFFFFFFFFu) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, bytes, 0x00020000);
 }
 
+// The three streams a wave reads: its row block's tile blocks, the table slices and the group sums.
+struct Streams {
+    const uint8_t *w, *t, *s;
+    uint32_t w_bytes, t_bytes, s_bytes;
+};
+
+// Requests tile kt.  With `live` false nothing is fetched and the stage reads as zeros: the caller
+// needs no branch around the request, so a tile's lookups and the next request stay one basic block.
 template <int B, int NP, int GQ, bool HZ>
-__device__ __forceinline__ void issue_tile(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, rsrc_t rw, rsrc_t rt,
-                                           rsrc_t rs, int kt, int lane) {
+__device__ __forceinline__ void issue_tile(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, const Streams& src, bool live,
+                                           int kt, int lane) {
     using Cfg = GemvCfg<B, NP, GQ, HZ>;
+    const rsrc_t rw = make_rsrc(src.w, live ? src.w_bytes : 0u);
+    const rsrc_t rt = make_rsrc(src.t, live ? src.t_bytes : 0u);
+    const rsrc_t rs = make_rsrc(src.s, live ? src.s_bytes : 0u);
     const int so = kt * Cfg::TB;  // scalar offset of the tile block inside the row block
 #pragma unroll
     for (int v = 0; v < B; ++v) s.c[v] = __builtin_amdgcn_raw_buffer_load_b128(rw, v * 1024 + lane * 16, so, kStreamAux);
@@ -208,9 +219,9 @@ __device__ __forceinline__ void issue_tile(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::
     const int to = kt * Cfg::T_BYTES;
 #pragma unroll
     for (int q = 0; q < NP; ++q) s.tt[q] = __builtin_amdgcn_raw_buffer_load_b128(rt, q * 1024 + lane * 16, to, 0);
-    s.sv = 0.f;
-    if (lane < Cfg::S_FLOATS)
-        s.sv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, lane * 4, kt * Cfg::S_FLOATS * 4, 0));
+    // every lane loads one float from the tile's group sums on (no divergent branch: the tile's code
+    // stays one basic block); `rs` ends with the array, lanes reaching past it read zero
+    s.sv = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (kt * Cfg::S_FLOATS + lane) * 4, 0, 0));
 }
 
 // A table entry as it comes out of LDS: NP fp16 values (the NP tokens of one pattern).
@@ -249,7 +260,7 @@ __device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, G
     wave_lds_sync();  // every lane is done reading the previous slice
 #pragma unroll
     for (int q = 0; q < NP; ++q) store_lds<u32x4>(lds + q * 1024 + lane * 16, s.tt[q]);
-    if (lane < Cfg::S_FLOATS) store_lds<float>(lds + Cfg::T_BYTES + lane * 4, s.sv);
+    store_lds<float>(lds + Cfg::T_BYTES + lane * 4, s.sv);  // the first S_FLOATS lanes hold the tile's sums
     wave_lds_sync();
 
     uint32_t base_v = lds;
@@ -304,7 +315,10 @@ __device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, G
                 for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(2.f, a[n], -load_lds<float>(sg + n * 4)), y[n]);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);  // keep the pipeline order: bounds the live registers
+        // keep the pipeline order, which bounds the live registers: the first stops the compiler from
+        // collecting the lookups of later words up front, the second the instruction scheduler
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -346,14 +360,18 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
     const int per_wave = (k1 - k0 + kWaves - 1) / kWaves;
     const int t0 = min(k0 + wave * per_wave, k1);  // this wave's K tiles [t0, t1)
     const int t1 = min(t0 + per_wave, k1);
-    const rsrc_t rw = make_rsrc(uniform(d.tiles) + (size_t)rb * n_ktiles * Cfg::TB);  // this row block's tiles
-    const rsrc_t rt = make_rsrc(uniform(d.lut_t));
-    const rsrc_t rs = make_rsrc(uniform(d.lut_s));
+    Streams src;
+    src.w = uniform(d.tiles) + (size_t)rb * n_ktiles * Cfg::TB;  // this row block's tiles
+    src.t = uniform(d.lut_t);
+    src.s = uniform(d.lut_s);
+    src.w_bytes = (uint32_t)(n_ktiles * Cfg::TB);
+    src.t_bytes = (uint32_t)(n_ktiles * Cfg::T_BYTES);
+    src.s_bytes = (uint32_t)(n_ktiles * Cfg::S_FLOATS * 4);
 
     Stage<B, NP, Cfg::MPL> st[D] = {};
 #pragma unroll
     for (int s = 0; s < D; ++s)
-        if (t0 + s < t1) issue_tile<B, NP, GQ, HZ>(st[s], rw, rt, rs, t0 + s, lane);
+        issue_tile<B, NP, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
 
     float y[NP];
 #pragma unroll
@@ -373,8 +391,7 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
                     else __builtin_amdgcn_s_setprio(0);
                 }
                 consume_tile<B, NP, GQ, HZ>(st[s], lds, lane, pw, y);
-                if (t + D < t1)
-                    issue_tile<B, NP, GQ, HZ>(st[s], rw, rt, rs, t + D, lane);
+                issue_tile<B, NP, GQ, HZ>(st[s], src, t + D < t1, t + D, lane);
             }
         }
     }
