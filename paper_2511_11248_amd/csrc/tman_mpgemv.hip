@@ -26,6 +26,8 @@
 // though one layer alone is too small.
 #include <hip/hip_fp16.h>
 
+#include <type_traits>
+
 #include "tman_internal.h"
 
 namespace tman {
@@ -167,6 +169,21 @@ __device__ __forceinline__ uint32_t or_byte(uint32_t base, uint32_t x) {
     return r;
 }
 
+// byte K of x, zero extended, in one full-rate VALU instruction
+template <int K>
+__device__ __forceinline__ uint32_t byte_of(uint32_t x) {
+    uint32_t r;
+    if constexpr (K == 0)
+        asm("v_and_b32 %0, 0xff, %1" : "=v"(r) : "v"(x));
+    else if constexpr (K == 3)
+        asm("v_lshrrev_b32 %0, 24, %1" : "=v"(r) : "v"(x));
+    else if constexpr (K == 1)
+        asm("v_bfe_u32 %0, %1, 8, 8" : "=v"(r) : "v"(x));
+    else
+        asm("v_bfe_u32 %0, %1, 16, 8" : "=v"(r) : "v"(x));
+    return r;
+}
+
 // a uniform float the compiler cannot constant-fold, so x * w + acc with fp16 x stays one
 // mixed-precision FMA also for w == 1
 __device__ __forceinline__ float opaque(float v) {
@@ -241,8 +258,10 @@ __device__ __forceinline__ void accumulate(const typename EntryT<NP>::type& e, f
     }
 }
 
-// Lookups of one tile block for the lane's row.  `lds` is the LDS address of the wave's private slot
-// (a multiple of 256, so index bits can be OR-ed in).  The 4*B plane words of the tile are handled
+// Lookups of one tile block for the lane's row.  `lds` is the LDS address of the wave's private slot;
+// the callers make it a link-time constant (one copy of the code per wave of the workgroup), so it
+// folds, together with the table's offset, into the immediate offset of the LDS load and the address
+// register is just the index byte.  The 4*B plane words of the tile are handled
 // one after the other, software pipelined: the eight lookups of word w+1 are issued before the eight
 // results of word w are accumulated, so LDS latency overlaps the arithmetic with few live registers.
 template <int B, int NP, int GQ, bool HZ>
@@ -263,8 +282,6 @@ __device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, G
     store_lds<float>(lds + Cfg::T_BYTES + lane * 4, s.sv);  // the first S_FLOATS lanes hold the tile's sums
     wave_lds_sync();
 
-    uint32_t base_v = lds;
-    asm("" : "+v"(base_v));  // the sub-dword OR wants its operands in vector registers
 
     // word wi: 32-weight block kb32 = wi / B of the tile, bit-plane i = wi % B
     auto fetch = [&](int wi, entry_t (&e)[8]) {
@@ -277,14 +294,14 @@ __device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, G
         // bytes of xe, odd nibbles in the bytes of xo
         const uint32_t xe = (w << SH) & NIB;
         const uint32_t xo = SH == 4 ? (w & NIB) : ((w >> (4 - SH)) & NIB);
-        e[0] = load_lds<entry_t>(or_byte<0>(base_v, xe) + (tb + 0 * TSTRIDE));
-        e[1] = load_lds<entry_t>(or_byte<0>(base_v, xo) + (tb + 1 * TSTRIDE));
-        e[2] = load_lds<entry_t>(or_byte<1>(base_v, xe) + (tb + 2 * TSTRIDE));
-        e[3] = load_lds<entry_t>(or_byte<1>(base_v, xo) + (tb + 3 * TSTRIDE));
-        e[4] = load_lds<entry_t>(or_byte<2>(base_v, xe) + (tb + 4 * TSTRIDE));
-        e[5] = load_lds<entry_t>(or_byte<2>(base_v, xo) + (tb + 5 * TSTRIDE));
-        e[6] = load_lds<entry_t>(or_byte<3>(base_v, xe) + (tb + 6 * TSTRIDE));
-        e[7] = load_lds<entry_t>(or_byte<3>(base_v, xo) + (tb + 7 * TSTRIDE));
+        e[0] = load_lds<entry_t>(byte_of<0>(xe) + (lds + tb + 0 * TSTRIDE));
+        e[1] = load_lds<entry_t>(byte_of<0>(xo) + (lds + tb + 1 * TSTRIDE));
+        e[2] = load_lds<entry_t>(byte_of<1>(xe) + (lds + tb + 2 * TSTRIDE));
+        e[3] = load_lds<entry_t>(byte_of<1>(xo) + (lds + tb + 3 * TSTRIDE));
+        e[4] = load_lds<entry_t>(byte_of<2>(xe) + (lds + tb + 4 * TSTRIDE));
+        e[5] = load_lds<entry_t>(byte_of<2>(xo) + (lds + tb + 5 * TSTRIDE));
+        e[6] = load_lds<entry_t>(byte_of<3>(xe) + (lds + tb + 6 * TSTRIDE));
+        e[7] = load_lds<entry_t>(byte_of<3>(xo) + (lds + tb + 7 * TSTRIDE));
     };
 
     entry_t e[2][8];
@@ -340,7 +357,6 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)slots)) + wave * Cfg::SLOT;
     float pw[B];  // plane weights 2^i: "shift and accumulate"
 #pragma unroll
     for (int i = 0; i < B; ++i) pw[i] = opaque((float)(1 << i));
@@ -368,32 +384,43 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
     src.t_bytes = (uint32_t)(n_ktiles * Cfg::T_BYTES);
     src.s_bytes = (uint32_t)(n_ktiles * Cfg::S_FLOATS * 4);
 
-    Stage<B, NP, Cfg::MPL> st[D] = {};
-#pragma unroll
-    for (int s = 0; s < D; ++s)
-        issue_tile<B, NP, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
-
     float y[NP];
 #pragma unroll
     for (int n = 0; n < NP; ++n) y[n] = 0.f;
 
-    for (int base = t0; base < t1; base += D) {
+    // The wave's tiles, with the LDS address of its slot known to the compiler (see consume_tile).
+    auto stream_tiles = [&](auto wave_tag) {
+        constexpr int WAVE = decltype(wave_tag)::value;
+        const uint32_t lds = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)slots)) + WAVE * Cfg::SLOT;
+        Stage<B, NP, Cfg::MPL> st[D] = {};
 #pragma unroll
-        for (int s = 0; s < D; ++s) {
-            const int t = base + s;
-            if (t < t1) {
-                {   // the more tiles a wave still has to do, the higher its issue priority: the waves
-                    // of a SIMD then finish together instead of leaving the youngest to run alone
-                    const int rem = t1 - t;
-                    if (rem >= 7) __builtin_amdgcn_s_setprio(3);
-                    else if (rem >= 5) __builtin_amdgcn_s_setprio(2);
-                    else if (rem >= 3) __builtin_amdgcn_s_setprio(1);
-                    else __builtin_amdgcn_s_setprio(0);
+        for (int s = 0; s < D; ++s)
+            issue_tile<B, NP, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
+        for (int base = t0; base < t1; base += D) {
+#pragma unroll
+            for (int s = 0; s < D; ++s) {
+                const int t = base + s;
+                if (t < t1) {
+                    {   // the more tiles a wave still has to do, the higher its issue priority: the waves
+                        // of a SIMD then finish together instead of leaving the youngest to run alone
+                        const int rem = t1 - t;
+                        if (rem >= 7) __builtin_amdgcn_s_setprio(3);
+                        else if (rem >= 5) __builtin_amdgcn_s_setprio(2);
+                        else if (rem >= 3) __builtin_amdgcn_s_setprio(1);
+                        else __builtin_amdgcn_s_setprio(0);
+                    }
+                    consume_tile<B, NP, GQ, HZ>(st[s], lds, lane, pw, y);
+                    issue_tile<B, NP, GQ, HZ>(st[s], src, t + D < t1, t + D, lane);
                 }
-                consume_tile<B, NP, GQ, HZ>(st[s], lds, lane, pw, y);
-                issue_tile<B, NP, GQ, HZ>(st[s], src, t + D < t1, t + D, lane);
             }
         }
+    };
+    static_assert(kWaves == 4, "one copy of the tile loop per wave");
+    switch (wave) {
+        case 0: stream_tiles(std::integral_constant<int, 0>{}); break;
+        case 1: stream_tiles(std::integral_constant<int, 1>{}); break;
+        case 2: stream_tiles(std::integral_constant<int, 2>{}); break;
+        default: stream_tiles(std::integral_constant<int, 3>{}); break;
     }
 
     // the four quarters of the segment meet in LDS
