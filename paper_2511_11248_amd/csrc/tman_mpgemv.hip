@@ -87,8 +87,9 @@ struct GemvCfg {
     static constexpr int T_BYTES = kTableBytesPerKTile * NP;
     static constexpr int S_FLOATS = GPT * NP;
     static constexpr int SLOT = T_BYTES + 256;  // table slice + group sums, per wave (multiple of 256)
-    // tile blocks in flight per wave, sized by registers: a stage is 4B + 4NP + <=5 VGPRs
-    static constexpr int D = (NP >= 8) ? 1 : (NP == 4 ? 2 : (B == 4 ? 2 : (B == 2 ? 3 : 4)));
+    // tile blocks in flight per wave.  Measured: more do not help (the waves of a compute unit together
+    // keep enough requests in flight) and cost time.
+    static constexpr int D = NP >= 4 ? 1 : (B == 4 ? 1 : (B == 2 ? 2 : 3));
 };
 
 template <int B, int NP, int MPL>
