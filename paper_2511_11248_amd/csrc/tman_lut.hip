@@ -12,8 +12,8 @@
 //   fp32 element  G * NP + n                    at byte offset n_ktiles * 1024 * NP, G < n_ktiles * 128 / group
 // so the slice of one K tile is contiguous and can be copied to LDS as it is.
 //
-// One launch serves up to 16 activations (the distinct inputs of a decode step): every workgroup
-// finds its activation by its block index; a thread builds one table of one token and takes part in
+// One launch serves up to 16 activations (the distinct inputs of a decode step): the second grid
+// dimension is the activation; a thread builds one table of one token and takes part in
 // the sum of its quantization block.
 #include <hip/hip_fp16.h>
 
@@ -26,7 +26,6 @@ struct LutJob {
     _Float16* T;
     float* S;
     int K, n_tables;
-    int block_begin;  // first block of this activation in the launch
 };
 struct LutJobs {
     LutJob job[16];
@@ -38,13 +37,11 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 // One thread per (table j, token n).  Consecutive lanes own consecutive tables of one token, so the
 // group sum of a quantization block (group / 4 tables) is a butterfly over adjacent lanes.
 __global__ void __launch_bounds__(256) build_lut_kernel(LutJobs a) {
-    int ji = 0;
-#pragma unroll 1
-    for (int i = 1; i < a.count; ++i)
-        if ((int)blockIdx.x >= a.job[i].block_begin) ji = i;
-    const LutJob& jb = a.job[ji];
+    // grid = (blocks of the longest activation) x (activations): no search for the job
+    const LutJob& jb = a.job[blockIdx.y];
     const int N = a.N, NP = a.NP, K = jb.K;
-    const int tid = ((int)blockIdx.x - jb.block_begin) * 256 + threadIdx.x;
+    if ((int)blockIdx.x * 256 >= jb.n_tables * NP) return;
+    const int tid = (int)blockIdx.x * 256 + threadIdx.x;
     const int n = tid / jb.n_tables, j = tid % jb.n_tables;  // n_tables is a multiple of 32
     const bool live = n < NP;
     float v[4] = {0.f, 0.f, 0.f, 0.f};
@@ -97,7 +94,7 @@ int launch_build_lut_batch(int count, const void* const* x, int N, const int* K,
         a.N = N;
         a.NP = NP;
         a.group = group;
-        int blocks = 0;
+        int blocks = 0;  // of the longest activation
         for (int i = 0; i < 16; ++i) {
             const int src = i0 + (i < a.count ? i : 0);
             const int nkt = (K[src] + kKTile - 1) / kKTile;
@@ -107,10 +104,10 @@ int launch_build_lut_batch(int count, const void* const* x, int N, const int* K,
             jb.S = reinterpret_cast<float*>(static_cast<uint8_t*>(lut[src]) + (size_t)nkt * kTableBytesPerKTile * NP);
             jb.K = K[src];
             jb.n_tables = nkt * kTablesPerKTile;
-            jb.block_begin = blocks;
-            if (i < a.count) blocks += (jb.n_tables * NP + 255) / 256;
+            const int b = (jb.n_tables * NP + 255) / 256;
+            if (i < a.count && b > blocks) blocks = b;
         }
-        hipLaunchKernelGGL(build_lut_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(build_lut_kernel, dim3((unsigned)blocks, (unsigned)a.count), dim3(256), 0, st, a);
     }
     return launch_status();
 }
