@@ -12,7 +12,7 @@
 //   fp32 element  G * NP + n                    at byte offset n_ktiles * 1024 * NP, G < n_ktiles * 128 / group
 // so the slice of one K tile is contiguous and can be copied to LDS as it is.
 //
-// One launch serves up to 16 activations (the distinct inputs of a decode step): the second grid
+// One launch serves up to 8 activations (the distinct inputs of a decode step): the second grid
 // dimension is the activation; a thread builds one table of one token and takes part in
 // the sum of its quantization block.
 #include <hip/hip_fp16.h>
@@ -27,8 +27,9 @@ struct LutJob {
     float* S;
     int K, n_tables;
 };
+constexpr int kLutJobsPerLaunch = 8;  // kernel arguments stay small
 struct LutJobs {
-    LutJob job[16];
+    LutJob job[kLutJobsPerLaunch];
     int count, N, NP, group;
 };
 
@@ -88,14 +89,14 @@ __global__ void __launch_bounds__(256) build_lut_kernel(LutJobs a) {
 int launch_build_lut_batch(int count, const void* const* x, int N, const int* K, int group, void* const* lut,
                            hipStream_t st) {
     const int NP = padded_tokens(N);
-    for (int i0 = 0; i0 < count; i0 += 16) {
+    for (int i0 = 0; i0 < count; i0 += kLutJobsPerLaunch) {
         LutJobs a;
-        a.count = count - i0 < 16 ? count - i0 : 16;
+        a.count = count - i0 < kLutJobsPerLaunch ? count - i0 : kLutJobsPerLaunch;
         a.N = N;
         a.NP = NP;
         a.group = group;
         int blocks = 0;  // of the longest activation
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < kLutJobsPerLaunch; ++i) {
             const int src = i0 + (i < a.count ? i : 0);
             const int nkt = (K[src] + kKTile - 1) / kKTile;
             LutJob& jb = a.job[i];

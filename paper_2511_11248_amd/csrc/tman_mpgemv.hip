@@ -100,10 +100,17 @@ struct Stage {
     float sv;                      // one group sum (lanes < S_FLOATS)
 };
 
+// kernel arguments: the descriptor itself for a single GEMV, the device table for a batch
 template <bool SINGLE>
-struct KernelArgs {
-    GemvDesc single;        // used when SINGLE
-    const GemvDesc* descs;  // device table otherwise
+struct KernelArgs;
+template <>
+struct KernelArgs<true> {
+    GemvDesc single;
+    int n_gemv;  // 1
+};
+template <>
+struct KernelArgs<false> {
+    const GemvDesc* descs;
     int n_gemv;
 };
 
@@ -526,7 +533,6 @@ int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, v
                   hipStream_t st) {
     KernelArgs<true> a;
     fill_desc(a.single, L, packed, lut, N, y, workspace, 0);
-    a.descs = nullptr;
     a.n_gemv = 1;
     return launch_format<true>(L.bits, L.has_zero, padded_tokens(N), L.group, a, plan_gemv(L, N).n_workgroups, st);
 }
@@ -534,7 +540,6 @@ int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, v
 int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,
                         int max_workgroups, hipStream_t st) {
     KernelArgs<false> a;
-    a.single = GemvDesc{};
     a.descs = descs_dev;
     a.n_gemv = n_gemv;
     return launch_format<false>(bits, has_zero, padded_tokens(N), group, a, max_workgroups, st);

@@ -55,7 +55,7 @@ def test_batched_build_matches_single_calls(oracle_lib):
     from gpu_helpers import dev, to_dev
 
     N, group = 3, 64
-    Ks = [512, 4096, 11008, 64]
+    Ks = [512, 4096, 11008, 64, 128, 2816, 192, 1024, 64, 320, 8192]  # more than one launch's worth of jobs
     xs = [to_dev(synth.normal_fp16(990 + i, N * K).reshape(N, K)) for i, K in enumerate(Ks)]
     single = [build_lut(x, group) for x in xs]
     luts = [torch.full((tman.tman_lut_bytes(N, K, group),), 0x77, dtype=torch.uint8, device=dev()) for K in Ks]
