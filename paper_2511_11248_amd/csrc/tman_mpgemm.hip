@@ -212,7 +212,6 @@ __device__ __forceinline__ void dequant_to_lds(const WRegs<B>& r, uint8_t* wrow)
 // not padded, so chunk c of token row R is kept at position c ^ ((R >> 2) & 3) of its row: the MFMA
 // operand reads of 16 consecutive rows then fall into 16 different 16-byte bank groups.  The
 // permutation is applied on the global-address side, where every lane is free to pick its source.
-constexpr int kXLoads = 4;  // wave instructions per producer wave and stage (16 in all)
 
 // Workgroup = 12 waves, three per SIMD.  Waves 0..7 are consumers: wave (wm, wn) owns 32 RB rows x 64
 // tokens of the tile and does nothing but read MFMA operands from LDS and issue MFMAs.  Waves 8..11
@@ -269,67 +268,102 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
         const int xrows = a.N - n0 < kTN ? a.N - n0 : kTN;
         const _Float16* xsrc = a.x + (size_t)n0 * a.K;
         const uint32_t xbytes = (uint32_t)xrows * (uint32_t)a.K * 2u;
-        // wave instruction i of this wave fills token rows 16 (4p + i) .. + 15; lane = 4 * row + position
-        uint32_t xvoff[kXLoads];
+        // Roles.  With four row blocks every producer wave dequantizes one and issues a quarter of the
+        // activation loads.  With fewer, wave 3 has no row block: it issues all activation loads (about 40
+        // cycles each) and the dequantizing waves none, which shortens the chain that gates a stage.
+        constexpr bool kSplitRoles = RB < 4;
+        constexpr int kLoaderWave = 3;
+        constexpr int kXAll = kTN / 16;  // activation loads of a stage (16 token rows each)
+        const uint32_t xlane = ((lane >> 2) * (uint32_t)a.K + ((lane & 3) ^ ((lane >> 4) & 3)) * 8u) * 2u;
+        const uint32_t x16rows = 16u * (uint32_t)a.K * 2u;  // bytes between the sources of consecutive loads
+        // load number i of a stage fills token rows 16 i .. 16 i + 15; lane = 4 * row + position
+        auto load_x = [&](int t, int first, int count) {
+            const rsrc_t rx = make_rsrc(xsrc, t < k_stages ? xbytes : 0u);
+            uint8_t* dst = smem + (t & (kRing - 1)) * T::StageBytes + T::WBytes;
 #pragma unroll
-        for (int i = 0; i < kXLoads; ++i) {
-            const uint32_t row = 16u * (4u * p + i) + (lane >> 2), chunk = (lane & 3) ^ ((lane >> 4) & 3);
-            xvoff[i] = (row * (uint32_t)a.K + chunk * 8u) * 2u;
-        }
-        const int xdst = T::WBytes + p * kXLoads * 1024;
+            for (int i = 0; i < kXAll; ++i)
+                if (i < count)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(dst + (first + i) * 1024),
+                                                             16, xlane + (uint32_t)(first + i) * x16rows, t * kStageK * 2, 0, 0);
+        };
         const int wdst = (p * 64 + lane) * kRowBytes;  // this lane's 64 bytes in the weight tile
 
         WRegs<B> wr[kSets];
-        // stage t: activations global -> ring.  Rows beyond N and stages beyond K are out of the buffer's
-        // range; whatever LDS holds for them only reaches outputs that are never stored, or is skipped.
-        auto load_x = [&](int t) {
-            const rsrc_t rx = make_rsrc(xsrc, t < k_stages ? xbytes : 0u);
-            uint8_t* dst = smem + (t & (kRing - 1)) * T::StageBytes + xdst;
-#pragma unroll
-            for (int i = 0; i < kXLoads; ++i)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(dst + i * 1024), 16,
-                                                         xvoff[i], t * kStageK * 2, 0, 0);
-        };
-        // stage t: packed weights global -> register set (all four waves issue the same number of loads,
-        // so that one count of outstanding loads fits all; a wave without a row block reads nothing)
+        // stage t: packed weights global -> register set (a wave without a row block reads nothing)
         auto load_wregs = [&](int set, int t) {
             load_w<B, GQ, HZ>(wr[set], make_rsrc(wsrc, t < k_stages && wvalid ? 0x7fffffffu : 0u), t >> 2, t & 3, lane);
         };
         auto w_to_lds = [&](int set, int t) {
             if (p < RB) dequant_to_lds<B, HZ>(wr[set], smem + (t & (kRing - 1)) * T::StageBytes + wdst);
         };
-        // prologue: stages 0 and 1 complete in the ring, activations of stage 2 on their way, weights of
-        // stages 2..5 in the register sets 2, 3, 0, 1
-        load_x(0);
-        load_x(1);
-        load_wregs(0, 0);
-        load_wregs(1, 1);
-        load_wregs(2, 2);
-        load_wregs(3, 3);
-        w_to_lds(0, 0);
-        w_to_lds(1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");  // all but the weights of stages 2 and 3 (two loads each)
-        load_x(2);
-        load_wregs(0, 4);
-        load_wregs(1, 5);
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        // During stage s: activations of stage s+3 -> ring (that buffer was last read in stage s-1),
-        // weights of stage s+2 registers -> ring, weights of stage s+6 global -> the same registers.
-        // Loads complete in order.  Before the barrier the activations of stage s+2 must have landed;
-        // they were issued first in stage s-1, so 8 loads are younger: 2 weight loads of stage s-1, 4
-        // activation loads and 2 weight loads of stage s.
-        for (int s = 0; s < n_stages; s += kSets) {
+        // Ring timing, any role: during stage s the activations of stage s+3 are requested (that buffer
+        // was last read in stage s-1), the weights of stage s+2 go registers -> ring and the weights of
+        // stage s+6 global -> the same registers.  Loads complete in order.  Before the barrier of stage
+        // s the activations of stage s+2 must have landed; they were issued first in stage s-1.
+        if (kSplitRoles && p == kLoaderWave) {
+            load_x(0, 0, kXAll);
+            load_x(1, 0, kXAll);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            load_x(2, 0, kXAll);
+            asm volatile("s_barrier" ::: "memory");
+            for (int s = 0; s < n_stages; ++s) {
+                load_x(s + 3, 0, kXAll);
+                // younger than the loads of stage s+2: the sixteen just issued
+                asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+            }
+        } else if (kSplitRoles) {
+            load_wregs(0, 0);
+            load_wregs(1, 1);
+            load_wregs(2, 2);
+            load_wregs(3, 3);
+            w_to_lds(0, 0);
+            w_to_lds(1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_wregs(0, 4);
+            load_wregs(1, 5);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            for (int s = 0; s < n_stages; s += kSets) {
 #pragma unroll
-            for (int u = 0; u < kSets; ++u) {
-                load_x(s + u + 3);
-                __builtin_amdgcn_sched_barrier(0);
-                w_to_lds((u + 2) % kSets, s + u + 2);
-                __builtin_amdgcn_sched_barrier(0);
-                load_wregs((u + 2) % kSets, s + u + 6);
-                __builtin_amdgcn_sched_barrier(0);
-                asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                for (int u = 0; u < kSets; ++u) {
+                    w_to_lds((u + 2) % kSets, s + u + 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_wregs((u + 2) % kSets, s + u + 6);
+                    __builtin_amdgcn_sched_barrier(0);
+                    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                }
+            }
+        } else {
+            // prologue: stages 0 and 1 complete in the ring, activations of stage 2 on their way, weights
+            // of stages 2..5 in the register sets 2, 3, 0, 1
+            load_x(0, 4 * p, 4);
+            load_x(1, 4 * p, 4);
+            load_wregs(0, 0);
+            load_wregs(1, 1);
+            load_wregs(2, 2);
+            load_wregs(3, 3);
+            w_to_lds(0, 0);
+            w_to_lds(1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");  // all but the weights of stages 2 and 3 (two loads each)
+            load_x(2, 4 * p, 4);
+            load_wregs(0, 4);
+            load_wregs(1, 5);
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            for (int s = 0; s < n_stages; s += kSets) {
+#pragma unroll
+                for (int u = 0; u < kSets; ++u) {
+                    load_x(s + u + 3, 4 * p, 4);
+                    __builtin_amdgcn_sched_barrier(0);
+                    w_to_lds((u + 2) % kSets, s + u + 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_wregs((u + 2) % kSets, s + u + 6);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // younger than the activation loads of stage s+2: 2 weight loads of stage s-1, 4
+                    // activation loads and 2 weight loads of stage s
+                    asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                }
             }
         }
         // loads of stages past the end may still be on their way to LDS, which the epilogue reuses
