@@ -46,7 +46,9 @@ constexpr int kWaves = 4;  // waves per workgroup
 GemvPlan plan_gemv(const Layout& L, int N) {
     GemvPlan p;
     p.np = padded_tokens(N);
-    p.n_seg = (L.n_ktiles + kGemvSegmentTiles - 1) / kGemvSegmentTiles;
+    // with four or eight tokens a tile takes 2 - 3 times as long: shorter segments, more workgroups (measured)
+    const int max_seg = p.np >= 4 ? kGemvSegmentTiles / 2 : kGemvSegmentTiles;
+    p.n_seg = (L.n_ktiles + max_seg - 1) / max_seg;
     p.seg_tiles = (L.n_ktiles + p.n_seg - 1) / p.n_seg;
     p.n_seg = (L.n_ktiles + p.seg_tiles - 1) / p.seg_tiles;
     p.n_workgroups = L.n_row_blocks * p.n_seg;
