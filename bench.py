@@ -31,8 +31,8 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # WRITE_SIZE runs of this script scaled by a plain copy of known size (--calibration-copy); the counters
 # cannot be read from inside the process.  Source: profiles/mpgemv_7b_w2g64_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    ("mpgemv", "7b_w2g64", 1): 64_947_200 + 142_336,
-    ("mpgemm", "prefill_w4g64", 1024): 92_633_088 + 22_544_384,
+    ("mpgemv", "7b_w2g64", 1): 65_122_304 + 142_336,
+    ("mpgemm", "prefill_w4g64", 1024): 92_630_221 + 22_544_384,
 }
 
 
