@@ -13,7 +13,7 @@
 // Scheduling.  A decode GEMV streams each weight byte once and a whole layer lasts microseconds, so
 // the kernel is organised around keeping HBM requests in flight and around short dependency chains:
 //   - a workgroup of four waves owns one row block (64 rows) and one K segment of at most 32 tiles;
-//     each wave takes a quarter of the segment and walks it with a ring of D tile blocks in flight
+//     each wave takes a quarter of the segment and walks it with one or two tile blocks in flight
 //     (coalesced 16-byte loads of the bit-plane chunks, the group parameters and the 1 KB table
 //     slice of the tile); the table slice goes to the wave's private LDS slot, so waves do not
 //     synchronise while streaming;
@@ -162,21 +162,6 @@ __device__ __forceinline__ T load_lds(uint32_t addr) {
 template <typename T>
 __device__ __forceinline__ void store_lds(uint32_t addr, T v) {
     *reinterpret_cast<lds_ptr<T>>(static_cast<uintptr_t>(addr)) = v;
-}
-
-// base | byte K of x, in one VALU instruction (sub-dword operand select)
-template <int K>
-__device__ __forceinline__ uint32_t or_byte(uint32_t base, uint32_t x) {
-    uint32_t r;
-    if constexpr (K == 0)
-        asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(base), "v"(x));
-    else if constexpr (K == 1)
-        asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(base), "v"(x));
-    else if constexpr (K == 2)
-        asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(base), "v"(x));
-    else
-        asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(base), "v"(x));
-    return r;
 }
 
 // byte K of x, zero extended, in one full-rate VALU instruction
