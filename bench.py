@@ -163,6 +163,27 @@ def main():
         "algorithmic_bytes_per_launch": int(bytes_per_launch),
     }
 
+    # context figures (not the headline): the same step on ONE copy of the layer set (63 MB: served by the
+    # 256 MB Infinity Cache), the bit-plane bytes alone, and what a plain device copy moves on this machine
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        lut_calls[0](stream)
+        gemv_calls[0](stream)
+    torch.cuda.synchronize()
+    hot_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
+    codes_bytes = sum(s.M * s.K * w.bits // 8 for s in shapes)
+    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        cp_dst.copy_(cp_src)
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2.0 * (1 << 30) / (time.perf_counter() - t0) / 1e9
+    del cp_src, cp_dst
+
     out = {
         "metric": "decode mpGEMV weight GB/s", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec_per_step * 1e3, 5),
@@ -170,7 +191,10 @@ def main():
         "config": {"workload": f"{w.name}: 7B-style layer set (qkv 12288x4096, o 4096x4096, gate/up 11008x4096, "
                                f"down 4096x11008), uint{w.bits} g{w.group}, N=1 decode, {n_inst} rotating copies; "
                                f"step = one launch building the {len(acts)} lookup tables + one batched GEMV launch",
-                   "weight_bytes_per_step": int(weight_bytes_per_step), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+                   "weight_bytes_per_step": int(weight_bytes_per_step), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+                   "codes_only_GBs": round(value * codes_bytes / weight_bytes_per_step, 1),
+                   "cache_resident_GBs": round(hot_value, 1),
+                   "device_copy_GBs_read_plus_write": round(copy_gbs, 1)},
         "roofline": roofline,
     }
 
