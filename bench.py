@@ -50,33 +50,18 @@ def parse():
     ap.add_argument("--event-every", type=int, default=8,
                     help="bracket every n-th launch of the dominant kernel with HIP events (each pair costs a few "
                          "microseconds of stream time, which would otherwise dominate a 20 us step)")
+    ap.add_argument("--table", action="store_true",
+                    help="instead of the headline line: time every configuration (decode workloads at their token "
+                         "counts, prefill at 256/1024/2048 tokens), check each against the CPU oracle, and print a table")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device-to-device copy of 256 MiB before the timed region: under "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its known traffic calibrates the counters")
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-
-    import paper_2511_11248_amd as tman
-    import synth
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    w = synth.WORKLOADS[args.workload]
-    n_inst = args.instances or w.instances
-    N = 1
-    # ------------------------------------------------------------------ inputs, resident in HBM
+def decode_job(torch, tman, synth, dev, w, N, n_inst):
+    """Everything one decode step of workload ``w`` needs, resident in HBM: ``n_inst`` packed copies of the
+    layer set, their activations, table buffers, outputs, and per copy the two bound launches of a step."""
     shapes = [tman.Shape(l.M, l.K, w.bits, w.group, w.has_zero) for l in w.layers]
     acts = []  # distinct activation tags in order of first use
     for l in w.layers:
@@ -115,6 +100,116 @@ def main():
     Ks = [w.layers[li0].K for li0 in act_layer0]
     lut_calls = [tman.bound_build_lut_batch(xs[inst], N, Ks, w.group, luts) for inst in range(n_inst)]
     gemv_calls = [tman.bound_mpgemv_batch_run(shapes, N, descs[inst]) for inst in range(n_inst)]
+    return {"shapes": shapes, "acts": acts, "weight_bytes_per_step": weight_bytes_per_step, "ys": ys,
+            "lut_calls": lut_calls, "gemv_calls": gemv_calls, "stream": stream,
+            "keep": (blobs, xs, luts, wss, descs)}  # the launches hold raw pointers into these
+
+
+def run_table(args, torch, tman, synth, dev):
+    """One row per configuration: GPU time, rate, fraction of the vendor peak, error against the fp64 CPU oracle
+    (row-normalised maximum), the oracle's own time on the host cores, and the ratio.  Decode rows rotate over
+    the workload's copies of the layer set (cold cache) and check copy 0; prefill rows check every 8th row."""
+    import oracle
+
+    oracle.build()
+    rows = []
+
+    def emit(r):
+        rows.append(r)
+        print("| " + " | ".join(str(c) for c in r) + " |", flush=True)
+
+    emit(["config", "GPU time (us)", "rate", "of vendor peak", "max err", "oracle time (ms)", "cores", "oracle/GPU"])
+    emit(["---"] * 8)
+    for name in ("tiny_w4g64", "7b_w2g64", "7b_w4g128", "3p8b_w2g64", "3p8b_w1g64"):
+        w = synth.WORKLOADS[name]
+        for N in w.tokens:
+            job = decode_job(torch, tman, synth, dev, w, N, w.instances)
+            n_inst, stream = w.instances, job["stream"]
+
+            def step(i):
+                job["lut_calls"][i % n_inst](stream)
+                job["gemv_calls"][i % n_inst](stream)
+
+            for i in range(args.warmup):
+                step(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                step(i)
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t0) / args.steps
+            # copy 0 against the oracle
+            step(0)
+            torch.cuda.synchronize()
+            err, cpu_t, used = 0.0, 0.0, 1
+            for li, s in enumerate(job["shapes"]):
+                q, sc, z = synth.layer_tensors(w, 0, li)
+                xh = synth.activation(w, 0, li, N)
+                c0 = time.perf_counter()
+                Y, used = oracle.matmul(q, sc, z, xh, w.bits, w.group, return_threads=True)
+                cpu_t += time.perf_counter() - c0
+                err = max(err, float(oracle.row_relative_error(job["ys"][li].cpu().numpy().astype(np.float64), Y).max()))
+            gbs = job["weight_bytes_per_step"] / sec / 1e9
+            emit([f"{name} N={N} ({n_inst} copies)", f"{sec * 1e6:.2f}", f"{gbs:.0f} GB/s",
+                  f"{gbs / HBM_PEAK_GBS:.1%}" if w.instances > 1 else "cache-resident", f"{err:.2e}",
+                  f"{cpu_t * 1e3:.0f}", used, f"{cpu_t / sec:.0f}x"])
+            del job
+    pw = synth.WORKLOADS["prefill_w4g64"]
+    spec = pw.layers[0]
+    ps = tman.Shape(spec.M, spec.K, pw.bits, pw.group, True)
+    q, sc, z = synth.layer_tensors(pw, 0, 0)
+    pblob = torch.empty(tman.tman_packed_bytes(ps), dtype=torch.uint8, device=dev)
+    tman.tman_pack_weights(ps, torch.from_numpy(q).to(dev), torch.from_numpy(sc).to(dev), torch.from_numpy(z).to(dev), pblob)
+    for NP in pw.tokens:
+        xh = synth.activation(pw, 0, 0, NP)
+        px = torch.from_numpy(xh).to(dev)
+        py = torch.empty((NP, spec.M), dtype=torch.float16, device=dev)
+        for _ in range(5):
+            tman.tman_mpgemm(ps, pblob, px, NP, py, None)
+        torch.cuda.synchronize()
+        reps = 50
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            tman.tman_mpgemm(ps, pblob, px, NP, py, None)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / reps
+        sub = slice(0, spec.M, 8)
+        c0 = time.perf_counter()
+        Y, used = oracle.matmul(np.ascontiguousarray(q[sub]), np.ascontiguousarray(sc[sub]), np.ascontiguousarray(z[sub]),
+                                xh, pw.bits, pw.group, return_threads=True)
+        cpu_t = (time.perf_counter() - c0) * 8
+        err = float(oracle.row_relative_error(py.cpu().numpy().astype(np.float64)[:, sub], Y).max())
+        tf = 2.0 * NP * spec.M * spec.K / sec / 1e12
+        emit([f"{pw.name} N={NP}", f"{sec * 1e6:.1f}", f"{tf:.0f} TFLOP/s", f"{tf / MFMA_F16_PEAK_TFLOPS:.1%}",
+              f"{err:.2e} (every 8th row)", f"{cpu_t * 1e3:.0f} (8 x the sampled rows)", used, f"{cpu_t / sec:.0f}x"])
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2511_11248_amd as tman
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.table:
+        run_table(args, torch, tman, synth, dev)
+        return
+
+    w = synth.WORKLOADS[args.workload]
+    n_inst = args.instances or w.instances
+    N = 1
+    job = decode_job(torch, tman, synth, dev, w, N, n_inst)
+    shapes, acts, weight_bytes_per_step = job["shapes"], job["acts"], job["weight_bytes_per_step"]
+    lut_calls, gemv_calls, stream = job["lut_calls"], job["gemv_calls"], job["stream"]
     events = []
 
     def step(i, record):
