@@ -156,7 +156,7 @@ int tman_mpgemm(const tman_shape_t *shape, const void *packed, const void *x, in
                 size_t workspace_bytes, void *stream);
 
 /*
- * Rows of W (output features) one workgroup of tman_mpgemm covers for this shape and N: 128, 192 or 256,
+ * Rows of W (output features) one workgroup of tman_mpgemm covers for this shape and N: 64, 128, 192 or 256,
  * chosen so that the workgroups fill the compute units of the current device best (256 units are
  * assumed when no device is present).  Informational; 0 for an invalid shape or N < 1.
  */

@@ -38,7 +38,7 @@ constexpr int kRing = 4;      // stage buffers in LDS
 constexpr int kSets = 4;      // register sets of the producers = stages of global loads in flight
 constexpr int kXcds = 8;      // workgroups are dealt to the chip's 8 XCDs (one L2 each) round robin
 
-// A workgroup covers RB row blocks (64 * RB output features) x 256 tokens; RB = 2, 3 or 4 is chosen
+// A workgroup covers RB row blocks (64 * RB output features) x 256 tokens; RB = 1 .. 4 is chosen
 // per call so that the number of workgroups fills the compute units best.
 template <int RB>
 struct Tile {
@@ -488,6 +488,9 @@ static int choose_row_blocks(int n_row_blocks, int N) {
         if (n_cu <= 0) n_cu = 256;
     }
     const int n_tiles = (N + kTN - 1) / kTN;
+    // A grid that leaves compute units idle even with one row block per workgroup: the time of a workgroup
+    // is then set by the chain load -> dequantize -> barrier of its stages, shortest with the smallest tile.
+    if ((long long)n_row_blocks * n_tiles <= n_cu) return 1;
     const double penalty[5] = {0, 0, 1.10, 1.03, 1.0};
     int best = 4;
     double best_cost = 1e30;
@@ -505,6 +508,7 @@ static int choose_row_blocks(int n_row_blocks, int N) {
 template <int B, int GQ, bool HZ>
 static int launch_cfg(const GemmArgs& a, hipStream_t st) {
     switch (choose_row_blocks(a.n_row_blocks, a.N)) {
+        case 1: return launch_tile<B, GQ, HZ, 1>(a, st);
         case 2: return launch_tile<B, GQ, HZ, 2>(a, st);
         case 3: return launch_tile<B, GQ, HZ, 3>(a, st);
         default: return launch_tile<B, GQ, HZ, 4>(a, st);

@@ -185,8 +185,12 @@ def test_batched_gemv_rejects_bad_arguments(lib):
 
 def test_prefill_tile_rows_query(lib):
     """The tile height follows the number of workgroups it yields (256 compute units assumed without a
-    device): small problems take the lowest tile, 768 / 1024 row blocks fill one round with 192 / 256 rows."""
-    assert tman.tman_mpgemm_tile_rows(tman.Shape(256, 512, 4, 64, True), 128) == 128
+    device): a grid of at most one workgroup per unit takes the lowest tile, 512 / 768 / 1024 row blocks fill
+    one round with 128 / 192 / 256 rows."""
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(256, 512, 4, 64, True), 128) == 64
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 256) == 64
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 512) == 128
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(32768, 384, 4, 64, True), 200) == 128
     assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 1024) == 192
     assert tman.tman_mpgemm_tile_rows(tman.Shape(49152, 384, 4, 64, True), 200) == 192
     assert tman.tman_mpgemm_tile_rows(tman.Shape(65536, 384, 4, 64, True), 200) == 256

@@ -84,10 +84,10 @@ def test_full_size_prefill_sampled_tokens(oracle_lib, N):
     assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
 
 
-@pytest.mark.parametrize("M,rows", [(49152, 192), (65536, 256)])
+@pytest.mark.parametrize("M,rows", [(16384, 64), (32768, 128), (49152, 192), (65536, 256)])
 def test_every_tile_height(oracle_lib, M, rows):
-    """Row counts that make the launcher pick the 192- and 256-row tiles (the small cases above all run
-    with 128 rows, the benchmark shape with 192); ragged token count, K = 12 stages so the stage ring
+    """Row counts that make the launcher pick each of its four tile heights (the small cases above all run
+    with 64 rows, the benchmark shape with 192); ragged token count, K = 12 stages so the stage ring
     wraps three times.  The oracle recomputes eight tokens in full."""
     K, bits, group, N = 384, 4, 64, 200
     shape = tman.Shape(M, K, bits, group, True)
