@@ -246,7 +246,9 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
     const int n0 = nt * kTN;
     // K is a multiple of the quantization group, hence of 32.  The loops run a multiple of four stages
     // (no conditional code between the loads and their use); a stage beyond K holds zero activations.
-    const int k_stages = a.K / kStageK, n_stages = (k_stages + kSets - 1) & ~(kSets - 1);
+    // (Eight with one row block, whose producers work in rounds of eight stages.)
+    constexpr int kRound = RB == 1 ? 2 * kSets : kSets;
+    const int k_stages = a.K / kStageK, n_stages = (k_stages + kRound - 1) & ~(kRound - 1);
 
     float16_t acc[RB][2];
 #pragma unroll
@@ -260,10 +262,12 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
     if (wave >= kConsumerWaves) {
         // ---------------------------------------------------------------- producer
         const int p = wave - kConsumerWaves;
-        const int rbw = mt * RB + p;
+        // the row block this wave dequantizes (with one row block per workgroup waves 0 and 1 share it)
+        const int pb = RB == 1 ? 0 : p;
+        const int rbw = mt * RB + pb;
         // the producers' short vector bursts gate every stage: issue them ahead of the consumers' MFMAs
         __builtin_amdgcn_s_setprio(3);
-        const bool wvalid = p < RB && rbw < a.n_row_blocks;
+        const bool wvalid = (RB == 1 ? p < 2 : p < RB) && rbw < a.n_row_blocks;
         const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? rbw : 0) * a.n_ktiles * TB;
         const int xrows = a.N - n0 < kTN ? a.N - n0 : kTN;
         const _Float16* xsrc = a.x + (size_t)n0 * a.K;
@@ -286,7 +290,7 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(dst + (first + i) * 1024),
                                                              16, xlane + (uint32_t)(first + i) * x16rows, t * kStageK * 2, 0, 0);
         };
-        const int wdst = (p * 64 + lane) * kRowBytes;  // this lane's 64 bytes in the weight tile
+        const int wdst = (pb * 64 + lane) * kRowBytes;  // this lane's 64 bytes in the weight tile
 
         WRegs<B> wr[kSets];
         // stage t: packed weights global -> register set (a wave without a row block reads nothing)
@@ -310,6 +314,81 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
                 load_x(s + 3, 0, kXAll);
                 // younger than the loads of stage s+2: the sixteen just issued
                 asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+            }
+        } else if constexpr (RB == 1) {
+            if (p < 2) {
+                // One row block: a stage is short, and what gates it is the chain load -> dequantize ->
+                // write -> barrier of a single wave.  Waves 0 and 1 take the even and the odd stages and
+                // spread the work of a stage over two stage slots (codes -> fp16 integers in registers
+                // during the first, the FMAs and the LDS writes during the second), in antiphase: in every
+                // slot one of them is in its first half and the other in its second.  Stage t is written
+                // during stage t-2, like in the other roles.
+                const uint32_t wlive = wvalid ? 0x7fffffffu : 0u;
+                uint8_t* const wrow = smem + wdst;
+                Dequant<B, HZ> dq;
+                auto load_own = [&](int set, int t) {  // t: a stage of this wave (p, p + 2, ...)
+                    load_w<B, GQ, HZ>(wr[set], make_rsrc(wsrc, t < k_stages ? wlive : 0u), t >> 2, t & 3, lane);
+                };
+                auto first_half = [&](int set) {
+                    dq.start(wr[set]);
+                    dq.insert();
+                };
+                auto second_half = [&](int t) {
+                    uint8_t* dst = wrow + (t & (kRing - 1)) * T::StageBytes;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) dq.emit(q, dst);
+                };
+                // prologue: this wave's first stage complete in the ring, its next four in the register sets;
+                // wave 0 also has the first half of stage 2 done
+#pragma unroll
+                for (int i = 0; i < kSets; ++i) load_own(i, p + 2 * i);
+                first_half(0);
+                second_half(p);
+                __builtin_amdgcn_sched_barrier(0);
+                load_own(0, p + 2 * kSets);
+                if (p == 0) {
+                    first_half(1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_own(1, 2 + 2 * kSets);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                // slots t (even) and t + 1.  Wave 0: second half of stage t+2, then first half of t+4.
+                // Wave 1: first half of stage t+3, then its second half.
+                if (p == 0) {
+                    for (int s = 0; s < n_stages; s += 2 * kSets) {
+#pragma unroll
+                        for (int u = 0; u < kSets; ++u) {
+                            const int t = s + 2 * u;
+                            second_half(t + 2);
+                            __builtin_amdgcn_sched_barrier(0);
+                            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                            first_half((u + 2) % kSets);  // stage t + 4, the wave's stage number t / 2 + 2
+                            __builtin_amdgcn_sched_barrier(0);
+                            load_own((u + 2) % kSets, t + 4 + 2 * kSets);
+                            __builtin_amdgcn_sched_barrier(0);
+                            asm volatile("s_barrier" ::: "memory");
+                        }
+                    }
+                } else {
+                    for (int s = 0; s < n_stages; s += 2 * kSets) {
+#pragma unroll
+                        for (int u = 0; u < kSets; ++u) {
+                            const int t = s + 2 * u;
+                            first_half((u + 1) % kSets);  // stage t + 3, the wave's stage number t / 2 + 1
+                            __builtin_amdgcn_sched_barrier(0);
+                            load_own((u + 1) % kSets, t + 3 + 2 * kSets);
+                            __builtin_amdgcn_sched_barrier(0);
+                            asm volatile("s_barrier" ::: "memory");
+                            second_half(t + 3);
+                            __builtin_amdgcn_sched_barrier(0);
+                            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                        }
+                    }
+                }
+            } else {  // wave 2 has no work: it only keeps the barriers
+                asm volatile("s_barrier" ::: "memory");
+                for (int s = 0; s < n_stages; ++s) asm volatile("s_barrier" ::: "memory");
             }
         } else if (kSplitRoles) {
             load_wregs(0, 0);
