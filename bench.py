@@ -2,8 +2,10 @@
 """Benchmark of the T-MAN hot path on one MI355X.
 
 Headline (the benchmark spec metric, configs[1]): decode mpGEMV weight GB/s on the 7B-style layer set,
-uint2 weights, group 64, N = 1.  One step = one pass over the layer set: the four lookup-table
-precomputes (one per distinct activation) and the five table-lookup GEMVs (qkv, o, gate, up, down).
+uint2 weights, group 64, N = 1.  One step = one pass over the layer set, activations in, outputs out:
+the lookup-table precompute and the five table-lookup GEMVs (qkv, o, gate, up, down), in one launch
+whose workgroups build the tables of their own K segment (the two-launch form, a table kernel followed
+by a lookup kernel, is timed beside it).
 To keep the 256 MB Infinity Cache from serving the weights, the steps rotate over 32 independent
 copies of the layer set (2 GB of packed weights); all inputs are resident in HBM before timing.
 
@@ -31,7 +33,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # WRITE_SIZE runs of this script scaled by a plain copy of known size (--calibration-copy); the counters
 # cannot be read from inside the process.  Source: profiles/mpgemv_7b_w2g64_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    ("mpgemv", "7b_w2g64", 1): 65_122_304 + 142_336,
+    ("mpgemv_x", "7b_w2g64", 1): 63_915_008 + 525_517,
     ("mpgemm", "prefill_w4g64", 1024): 92_630_221 + 22_544_384,
 }
 
@@ -39,8 +41,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--workload", default="7b_w2g64")
     ap.add_argument("--instances", type=int, default=0, help="copies of the layer set to rotate over (0 = workload default)")
     ap.add_argument("--prefill-tokens", type=int, default=1024)
@@ -100,9 +102,18 @@ def decode_job(torch, tman, synth, dev, w, N, n_inst):
     Ks = [w.layers[li0].K for li0 in act_layer0]
     lut_calls = [tman.bound_build_lut_batch(xs[inst], N, Ks, w.group, luts) for inst in range(n_inst)]
     gemv_calls = [tman.bound_mpgemv_batch_run(shapes, N, descs[inst]) for inst in range(n_inst)]
+    # one token: the lookup kernel can build its tables itself, which makes the step a single launch
+    x_calls, x_descs = None, []
+    if N == 1:
+        for inst in range(n_inst):
+            d = torch.empty(tman.tman_mpgemv_batch_desc_bytes(len(shapes)), dtype=torch.uint8, device=dev)
+            tman.tman_mpgemv_x_batch_prepare(shapes, blobs[inst], [xs[inst][a] for a in act_of_layer], ys, wss, d)
+            x_descs.append(d)
+        torch.cuda.synchronize()
+        x_calls = [tman.bound_mpgemv_x_batch_run(shapes, x_descs[inst]) for inst in range(n_inst)]
     return {"shapes": shapes, "acts": acts, "weight_bytes_per_step": weight_bytes_per_step, "ys": ys,
-            "lut_calls": lut_calls, "gemv_calls": gemv_calls, "stream": stream,
-            "keep": (blobs, xs, luts, wss, descs)}  # the launches hold raw pointers into these
+            "lut_calls": lut_calls, "gemv_calls": gemv_calls, "x_calls": x_calls, "stream": stream,
+            "keep": (blobs, xs, luts, wss, descs, x_descs)}  # the launches hold raw pointers into these
 
 
 def run_table(args, torch, tman, synth, dev):
@@ -127,8 +138,11 @@ def run_table(args, torch, tman, synth, dev):
             n_inst, stream = w.instances, job["stream"]
 
             def step(i):
-                job["lut_calls"][i % n_inst](stream)
-                job["gemv_calls"][i % n_inst](stream)
+                if job["x_calls"] is not None:  # one token: one launch
+                    job["x_calls"][i % n_inst](stream)
+                else:
+                    job["lut_calls"][i % n_inst](stream)
+                    job["gemv_calls"][i % n_inst](stream)
 
             for i in range(args.warmup):
                 step(i)
@@ -150,7 +164,7 @@ def run_table(args, torch, tman, synth, dev):
                 cpu_t += time.perf_counter() - c0
                 err = max(err, float(oracle.row_relative_error(job["ys"][li].cpu().numpy().astype(np.float64), Y).max()))
             gbs = job["weight_bytes_per_step"] / sec / 1e9
-            emit([f"{name} N={N} ({n_inst} copies)", f"{sec * 1e6:.2f}", f"{gbs:.0f} GB/s",
+            emit([f"{name} N={N} ({n_inst} copies, {'one launch' if job['x_calls'] is not None else 'two launches'})", f"{sec * 1e6:.2f}", f"{gbs:.0f} GB/s",
                   f"{gbs / HBM_PEAK_GBS:.1%}" if w.instances > 1 else "cache-resident", f"{err:.2e}",
                   f"{cpu_t * 1e3:.0f}", used, f"{cpu_t / sec:.0f}x"])
             del job
@@ -209,17 +223,17 @@ def main():
     N = 1
     job = decode_job(torch, tman, synth, dev, w, N, n_inst)
     shapes, acts, weight_bytes_per_step = job["shapes"], job["acts"], job["weight_bytes_per_step"]
-    lut_calls, gemv_calls, stream = job["lut_calls"], job["gemv_calls"], job["stream"]
+    lut_calls, gemv_calls, x_calls, stream = job["lut_calls"], job["gemv_calls"], job["x_calls"], job["stream"]
     events = []
 
     def step(i, record):
+        # activations in, outputs out: the table precompute and the lookups of all five GEMVs in one launch
         inst = i % n_inst
-        lut_calls[inst](stream)
         if record:
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
             e0.record()
-        gemv_calls[inst](stream)
+        x_calls[inst](stream)
         if record:
             e1.record()
             events.append((e0, e1))
@@ -251,8 +265,8 @@ def main():
     bytes_per_launch = weight_bytes_per_step
     achieved = bytes_per_launch / avg_launch_s / 1e9
     roofline = {
-        "bound": "hbm", "kernel": "mpgemv_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(("mpgemv", w.name, N)),
+        "bound": "hbm", "kernel": "mpgemv_x_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(("mpgemv_x", w.name, N)),
         "launches": n_launch, "avg_launch_us": round(avg_launch_s * 1e6, 3),
         "median_launch_us": round(gemv_ms[n_launch // 2] * 1e3, 3),
         "algorithmic_bytes_per_launch": int(bytes_per_launch),
@@ -263,10 +277,20 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        lut_calls[0](stream)
-        gemv_calls[0](stream)
+        x_calls[0](stream)
     torch.cuda.synchronize()
     hot_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
+    # the same step as two launches (table precompute kernel, then the lookup kernel reading its tables)
+    for i in range(args.warmup):
+        lut_calls[i % n_inst](stream)
+        gemv_calls[i % n_inst](stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        lut_calls[i % n_inst](stream)
+        gemv_calls[i % n_inst](stream)
+    torch.cuda.synchronize()
+    two_launch_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
     codes_bytes = sum(s.M * s.K * w.bits // 8 for s in shapes)
     cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     cp_dst = torch.empty_like(cp_src)
@@ -285,10 +309,12 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{w.name}: 7B-style layer set (qkv 12288x4096, o 4096x4096, gate/up 11008x4096, "
                                f"down 4096x11008), uint{w.bits} g{w.group}, N=1 decode, {n_inst} rotating copies; "
-                               f"step = one launch building the {len(acts)} lookup tables + one batched GEMV launch",
+                               f"step = one launch: every workgroup builds the lookup tables of its K segment "
+                               f"from the {len(acts)} activations, then does its lookups",
                    "weight_bytes_per_step": int(weight_bytes_per_step), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
                    "codes_only_GBs": round(value * codes_bytes / weight_bytes_per_step, 1),
                    "cache_resident_GBs": round(hot_value, 1),
+                   "two_launch_step_GBs": round(two_launch_value, 1),
                    "device_copy_GBs_read_plus_write": round(copy_gbs, 1)},
         "roofline": roofline,
     }

@@ -145,6 +145,29 @@ int tman_mpgemv_batch_prepare(int32_t count, const tman_shape_t *shapes, const v
 int tman_mpgemv_batch_run(int32_t count, const tman_shape_t *shapes, int32_t N, const void *desc, void *stream);
 
 /*
+ * Decoding mpGEMV of ONE token with the table precompute inside the lookup kernel (Sec. 2.2, Sec. 4.3 for
+ * the lookups; Sec. 5 moves the precompute into a kernel of its own because it is costly on the paper's
+ * hardware, whereas here a kernel boundary costs more than the precompute).  Every workgroup builds the
+ * tables of its own K segment (at most 3072 columns: 768 tables, 24 KB) in LDS from the activations,
+ * exactly as tman_build_lut computes them (fp32 sums in ascending order, one rounding to fp16; the same
+ * group sums), and then performs the same lookups as tman_mpgemv.  The result is what
+ * tman_build_lut + tman_mpgemv give for N = 1, up to the order of the fp32 additions across K.
+ *   x         : fp16 [K], device, 16-byte aligned
+ *   y         : fp16 [M]
+ *   workspace : tman_mpgemv_workspace_bytes(shape, 1) bytes, under the rules of tman_mpgemv (the size for
+ *               N = 1 covers both calls, but a workspace is used by one call at a time)
+ * The batch forms follow tman_mpgemv_batch_prepare / _run with `x` in place of `lut` (entries may repeat:
+ * Q/K/V, gate/up) and N fixed to 1; a descriptor table made by one prepare call is only valid for the run
+ * call of the same kind.
+ */
+int tman_mpgemv_x(const tman_shape_t *shape, const void *packed, const void *x, void *y, void *workspace,
+                  size_t workspace_bytes, void *stream);
+int tman_mpgemv_x_batch_prepare(int32_t count, const tman_shape_t *shapes, const void *const *packed,
+                                const void *const *x, void *const *y, void *const *workspace,
+                                const size_t *workspace_bytes, void *desc, void *stream);
+int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t *shapes, const void *desc, void *stream);
+
+/*
  * Prefill mpGEMM (Sec. 4.1 "Fused LUT-based dequantization", Sec. 4.2): bit-planes are repacked to
  * codes (level 1), each code is looked up in its quantization block's table
  * D[c] = fp16((c - zero) * scale) (level 2; sign form fp16((2c - 1) * scale)), and the fp16 weights

@@ -21,7 +21,11 @@ from .api import (  # noqa: F401
     tman_mpgemv_batch_desc_bytes,
     tman_mpgemv_batch_prepare,
     tman_mpgemv_batch_run,
+    tman_mpgemv_x,
+    tman_mpgemv_x_batch_prepare,
+    tman_mpgemv_x_batch_run,
     bound_build_lut_batch,
+    bound_mpgemv_x_batch_run,
     bound_mpgemv_batch_run,
     tman_status_string,
     tman_layout_version,

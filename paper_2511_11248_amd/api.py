@@ -80,6 +80,12 @@ def _load():
         L.tman_mpgemv_batch_prepare.argtypes = [C.c_int32, sp, vp, vp, C.c_int32, vp, vp, vp, vp, vp]
         L.tman_mpgemv_batch_run.restype = C.c_int
         L.tman_mpgemv_batch_run.argtypes = [C.c_int32, sp, C.c_int32, vp, vp]
+        L.tman_mpgemv_x.restype = C.c_int
+        L.tman_mpgemv_x.argtypes = [sp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.tman_mpgemv_x_batch_prepare.restype = C.c_int
+        L.tman_mpgemv_x_batch_prepare.argtypes = [C.c_int32, sp, vp, vp, vp, vp, vp, vp, vp]
+        L.tman_mpgemv_x_batch_run.restype = C.c_int
+        L.tman_mpgemv_x_batch_run.argtypes = [C.c_int32, sp, vp, vp]
         L.tman_mpgemm.restype = C.c_int
         L.tman_mpgemm.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
         L.tman_mpgemm_tile_rows.restype = C.c_int32
@@ -203,6 +209,26 @@ def tman_mpgemv_batch_run(shapes, N: int, desc, stream=None) -> None:
     _check(_load().tman_mpgemv_batch_run(n, cs, N, _ptr(desc), _stream(stream)), "tman_mpgemv_batch_run")
 
 
+def tman_mpgemv_x(shape: Shape, packed, x, y, workspace, stream=None) -> None:
+    """y fp16 [M] = x fp16 [K] * dequant(W)^T for one token; the lookup kernel builds its tables itself."""
+    wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
+    _check(_load().tman_mpgemv_x(C.byref(shape.c()), _ptr(packed), _ptr(x), _ptr(y), _ptr(workspace), wb,
+                                 _stream(stream)), "tman_mpgemv_x")
+
+
+def tman_mpgemv_x_batch_prepare(shapes, packed, xs, y, workspace, desc, stream=None) -> None:
+    """Descriptor table for a batch of one-token GEMVs that build their own tables (xs entries may repeat)."""
+    n, cs, pk, xx, yy, ws, wb = _batch_arrays(shapes, packed, xs, y, workspace)
+    _check(_load().tman_mpgemv_x_batch_prepare(n, cs, pk, xx, yy, ws, wb, _ptr(desc), _stream(stream)),
+           "tman_mpgemv_x_batch_prepare")
+
+
+def tman_mpgemv_x_batch_run(shapes, desc, stream=None) -> None:
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    _check(_load().tman_mpgemv_x_batch_run(n, cs, _ptr(desc), _stream(stream)), "tman_mpgemv_x_batch_run")
+
+
 def tman_build_lut_batch(xs, N: int, Ks, group: int, luts, stream=None) -> None:
     """Lookup tables for several activations (lists of equal length) in one launch."""
     n = len(xs)
@@ -232,5 +258,16 @@ def bound_mpgemv_batch_run(shapes, N: int, desc):
 
     def call(stream_handle):
         _check(fn(*args, stream_handle), "tman_mpgemv_batch_run")
+
+    return call
+
+
+def bound_mpgemv_x_batch_run(shapes, desc):
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    fn, args = _load().tman_mpgemv_x_batch_run, (n, cs, _ptr(desc))
+
+    def call(stream_handle):
+        _check(fn(*args, stream_handle), "tman_mpgemv_x_batch_run")
 
     return call

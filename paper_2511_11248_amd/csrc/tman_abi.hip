@@ -22,8 +22,14 @@ size_t tman_lut_bytes(int32_t N, int32_t K, int32_t group) {
 
 size_t tman_mpgemv_workspace_bytes(const tman_shape_t* shape, int32_t N) {
     if (check_shape(shape) != TMAN_OK || N < 1 || N > TMAN_MAX_DECODE_TOKENS) return 0;
-    GemvPlan p = plan_gemv(make_layout(shape), N);
-    return p.ticket_bytes + p.partial_bytes;
+    const Layout L = make_layout(shape);
+    GemvPlan p = plan_gemv(L, N);
+    size_t need = p.ticket_bytes + p.partial_bytes;
+    if (N == 1) {  // also serves tman_mpgemv_x, which cuts K into shorter segments
+        GemvPlan px = plan_gemv_x(L);
+        if (px.ticket_bytes + px.partial_bytes > need) need = px.ticket_bytes + px.partial_bytes;
+    }
+    return need;
 }
 
 size_t tman_mpgemm_workspace_bytes(const tman_shape_t* shape, int32_t N) {
@@ -144,6 +150,51 @@ int tman_mpgemv_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, 
     }
     return launch_mpgemv_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO, N,
                                static_cast<const GemvDesc*>(desc), count, max_wg, (hipStream_t)stream);
+}
+
+int tman_mpgemv_x(const tman_shape_t* shape, const void* packed, const void* x, void* y, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != TMAN_OK) return rc;
+    if (!packed || !x || !y) return TMAN_ERR_NULL;
+    if (!aligned16(packed) || !aligned16(x)) return TMAN_ERR_ALIGN;
+    size_t need = tman_mpgemv_workspace_bytes(shape, 1);
+    if (need && (!workspace || workspace_bytes < need)) return TMAN_ERR_WORKSPACE;
+    if (workspace && !aligned16(workspace)) return TMAN_ERR_ALIGN;
+    return launch_mpgemv_x(make_layout(shape), packed, x, y, workspace, (hipStream_t)stream);
+}
+
+int tman_mpgemv_x_batch_prepare(int32_t count, const tman_shape_t* shapes, const void* const* packed,
+                                const void* const* x, void* const* y, void* const* workspace,
+                                const size_t* workspace_bytes, void* desc, void* stream) {
+    int rc = check_batch(count, shapes, 1);
+    if (rc != TMAN_OK) return rc;
+    if (!packed || !x || !y || !workspace || !workspace_bytes || !desc) return TMAN_ERR_NULL;
+    if (!aligned16(desc)) return TMAN_ERR_ALIGN;
+    GemvDesc host[TMAN_MAX_BATCH];
+    for (int i = 0; i < count; ++i) {
+        if (!packed[i] || !x[i] || !y[i] || !workspace[i]) return TMAN_ERR_NULL;
+        if (!aligned16(packed[i]) || !aligned16(x[i]) || !aligned16(workspace[i])) return TMAN_ERR_ALIGN;
+        if (workspace_bytes[i] < tman_mpgemv_workspace_bytes(&shapes[i], 1)) return TMAN_ERR_WORKSPACE;
+        for (int j = 0; j < i; ++j)
+            if (workspace[j] == workspace[i]) return TMAN_ERR_WORKSPACE;  // every GEMV needs its own
+        fill_desc_x(host[i], make_layout(&shapes[i]), packed[i], x[i], y[i], workspace[i]);
+    }
+    return launch_write_descs(host, count, static_cast<GemvDesc*>(desc), (hipStream_t)stream);
+}
+
+int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t* shapes, const void* desc, void* stream) {
+    int rc = check_batch(count, shapes, 1);
+    if (rc != TMAN_OK) return rc;
+    if (!desc) return TMAN_ERR_NULL;
+    if (!aligned16(desc)) return TMAN_ERR_ALIGN;
+    int max_wg = 0;
+    for (int i = 0; i < count; ++i) {
+        const int n = plan_gemv_x(make_layout(&shapes[i])).n_workgroups;
+        if (n > max_wg) max_wg = n;
+    }
+    return launch_mpgemv_x_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO,
+                                 static_cast<const GemvDesc*>(desc), count, max_wg, (hipStream_t)stream);
 }
 
 int32_t tman_mpgemm_tile_rows(const tman_shape_t* shape, int32_t N) {

@@ -72,8 +72,8 @@ constexpr int kGemvSegmentTiles = 32;
 // One GEMV of a decode launch, as the kernel sees it.
 struct GemvDesc {
     const uint8_t* tiles;  // first tile block (past the header)
-    const uint8_t* lut_t;  // fp16 tables
-    const uint8_t* lut_s;  // fp32 group sums
+    const uint8_t* lut_t;  // fp16 tables; for the kernel that builds its own tables: the activations, fp16 [K]
+    const uint8_t* lut_s;  // fp32 group sums (unused by that kernel)
     void* y;               // fp16 [N][M]
     int32_t* tickets;      // [n_row_blocks], zero between launches
     float* partial;        // [n_row_blocks][n_seg][NP][64]
@@ -81,7 +81,7 @@ struct GemvDesc {
     int wg_begin;          // index of this GEMV's first workgroup in the launch
     int n_seg;             // K segments per row block
     int seg_tiles;         // tiles per segment (the last may be shorter)
-    int pad;
+    int K;                 // columns of W
 };
 
 struct GemvPlan {
@@ -91,6 +91,10 @@ struct GemvPlan {
     size_t partial_bytes;
 };
 GemvPlan plan_gemv(const Layout& L, int N);
+// Plan of the one-token kernel that builds its tables itself: shorter segments (less LDS for the
+// tables of a segment, more workgroups; measured).
+constexpr int kGemvXSegmentTiles = 24;
+GemvPlan plan_gemv_x(const Layout& L);
 void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
                int wg_begin);
 
@@ -105,6 +109,11 @@ int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, v
                   hipStream_t st);
 int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,
                         int max_workgroups, hipStream_t st);
+// one token, tables built inside the lookup kernel from the activations x (fp16 [K])
+void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x, void* y, void* workspace);
+int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y, void* workspace, hipStream_t st);
+int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
+                          hipStream_t st);
 int launch_write_descs(const GemvDesc* host, int count, GemvDesc* dev, hipStream_t st);
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);
 int mpgemm_row_blocks_per_workgroup(const Layout& L, int N);

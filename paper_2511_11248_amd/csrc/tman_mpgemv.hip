@@ -43,11 +43,9 @@ constexpr int kWaves = 4;  // waves per workgroup
 // ---------------------------------------------------------------------------------------------
 // host-side planning
 
-GemvPlan plan_gemv(const Layout& L, int N) {
+static GemvPlan plan_segments(const Layout& L, int np, int max_seg) {
     GemvPlan p;
-    p.np = padded_tokens(N);
-    // with four or eight tokens a tile takes 2 - 3 times as long: shorter segments, more workgroups (measured)
-    const int max_seg = p.np >= 4 ? kGemvSegmentTiles / 2 : kGemvSegmentTiles;
+    p.np = np;
     p.n_seg = (L.n_ktiles + max_seg - 1) / max_seg;
     p.seg_tiles = (L.n_ktiles + p.n_seg - 1) / p.n_seg;
     p.n_seg = (L.n_ktiles + p.seg_tiles - 1) / p.seg_tiles;
@@ -57,9 +55,16 @@ GemvPlan plan_gemv(const Layout& L, int N) {
     return p;
 }
 
-void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
-               int wg_begin) {
-    GemvPlan p = plan_gemv(L, N);
+GemvPlan plan_gemv(const Layout& L, int N) {
+    const int np = padded_tokens(N);
+    // with four or eight tokens a tile takes 2 - 3 times as long: shorter segments, more workgroups (measured)
+    return plan_segments(L, np, np >= 4 ? kGemvSegmentTiles / 2 : kGemvSegmentTiles);
+}
+
+GemvPlan plan_gemv_x(const Layout& L) { return plan_segments(L, 1, kGemvXSegmentTiles); }
+
+static void fill_desc_plan(GemvDesc& d, const Layout& L, const GemvPlan& p, const void* packed, const void* lut, int N,
+                           void* y, void* workspace, int wg_begin) {
     d.tiles = static_cast<const uint8_t*>(packed) + kHeaderBytes;
     d.lut_t = static_cast<const uint8_t*>(lut);
     d.lut_s = d.lut_t + (size_t)L.n_ktiles * kTableBytesPerKTile * p.np;
@@ -73,7 +78,17 @@ void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut
     d.wg_begin = wg_begin;
     d.n_seg = p.n_seg;
     d.seg_tiles = p.seg_tiles;
-    d.pad = 0;
+    d.K = L.K;
+}
+
+void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
+               int wg_begin) {
+    fill_desc_plan(d, L, plan_gemv(L, N), packed, lut, N, y, workspace, wg_begin);
+}
+
+void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x, void* y, void* workspace) {
+    fill_desc_plan(d, L, plan_gemv_x(L), packed, x, 1, y, workspace, 0);
+    d.lut_s = nullptr;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -343,6 +358,60 @@ __device__ __forceinline__ const GemvDesc& desc_of(const KernelArgs<SINGLE>& a, 
     }
 }
 
+// Output of one row block by its first wave: y holds the sums of the workgroup's K segment for the lane's
+// row.  With one segment they are the result; otherwise the segments meet through memory (see above).
+template <int NP>
+__device__ __forceinline__ void finish_rows(const GemvDesc& d, int rb, int seg, int n_seg, int lane, float (&y)[NP]) {
+    const int m = rb * kRows + lane;
+    const int M = d.M, N = d.N;
+    _Float16* out = static_cast<_Float16*>(d.y);
+    if (n_seg == 1) {
+        if (m < M) {
+#pragma unroll
+            for (int n = 0; n < NP; ++n)
+                if (n < N) out[(size_t)n * M + m] = (_Float16)y[n];
+        }
+        return;
+    }
+
+    // K longer than one segment: publish this segment's partial sums and take a ticket
+    float* base_p = d.partial + (size_t)rb * n_seg * NP * kRows;
+    float* mine = base_p + (size_t)seg * NP * kRows;
+#pragma unroll
+    for (int n = 0; n < NP; ++n)
+        __hip_atomic_store(mine + n * kRows + lane, y[n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the partials have reached device-coherent memory
+    int32_t* ticket = d.tickets + rb;
+    int prev = 0;
+    if (lane == 0) prev = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    prev = __builtin_amdgcn_readfirstlane(prev);
+    if (prev != n_seg - 1) return;
+    // last ticket: every segment of this row block has been published; add them in segment order
+    float acc[NP];
+#pragma unroll
+    for (int n = 0; n < NP; ++n) acc[n] = 0.f;
+    for (int p0 = 0; p0 < n_seg; p0 += 4) {
+        float v[4][NP];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int n = 0; n < NP; ++n)
+                v[q][n] = (p0 + q < n_seg) ? __hip_atomic_load(base_p + ((size_t)(p0 + q) * NP + n) * kRows + lane,
+                                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                           : 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int n = 0; n < NP; ++n) acc[n] += v[q][n];
+    }
+    if (m < M) {
+#pragma unroll
+        for (int n = 0; n < NP; ++n)
+            if (n < N) out[(size_t)n * M + m] = (_Float16)acc[n];
+    }
+    if (lane == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int B, int NP, int GQ, bool HZ, bool SINGLE>
 __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> a) {
     using Cfg = GemvCfg<B, NP, GQ, HZ>;
@@ -426,54 +495,217 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
 #pragma unroll
     for (int n = 0; n < NP; ++n) y[n] = ((red[0][n][lane] + red[1][n][lane]) + red[2][n][lane]) + red[3][n][lane];
 
-    const int m = rb * kRows + lane;
-    const int M = d.M, N = d.N;
-    _Float16* out = static_cast<_Float16*>(d.y);
-    if (n_seg == 1) {
-        if (m < M) {
+    finish_rows<NP>(d, rb, seg, n_seg, lane, y);
+}
+
+// ---------------------------------------------------------------------------------------------
+// One token, tables built in the kernel.
+//
+// With a single token the tables of a whole K segment (24 tiles = 768 tables = 24 KB) fit in LDS next
+// to three or four other workgroups.  The workgroup builds them itself from the activations of its
+// segment (6 KB) while its first weight tiles are on their way, so a decode step needs no launch for
+// the table precompute, no table traffic between the two kernels, and no per-tile copy of a table
+// slice into LDS.  The entries are computed exactly as build_lut_kernel computes them (fp32 sums in
+// ascending order, one rounding to fp16), as are the group sums (same butterfly).
+//
+// A lookup address is tile base | index byte: one v_perm_b32 takes byte k of the prepared index word as
+// byte 0 and bytes 1..3 of the tile's table base (a multiple of 1024), the table's place inside the
+// tile is the immediate offset of the LDS load.  One instruction per lookup, as in the kernel above.
+
+__device__ __forceinline__ uint32_t index_into(uint32_t idx_word, uint32_t base, uint32_t selector) {
+    uint32_t r;
+    asm("v_perm_b32 %0, %1, %2, %3" : "=v"(r) : "v"(idx_word), "v"(base), "s"(selector));
+    return r;
+}
+
+template <int B, int GQ, bool HZ>
+__device__ __forceinline__ void issue_weights(Stage<B, 1, GemvCfg<B, 1, GQ, HZ>::MPL>& s, const Streams& src, bool live,
+                                              int kt, int lane) {
+    using Cfg = GemvCfg<B, 1, GQ, HZ>;
+    const rsrc_t rw = make_rsrc(src.w, live ? src.w_bytes : 0u);
+    const int so = kt * Cfg::TB;
 #pragma unroll
-            for (int n = 0; n < NP; ++n)
-                if (n < N) out[(size_t)n * M + m] = (_Float16)y[n];
+    for (int v = 0; v < B; ++v) s.c[v] = __builtin_amdgcn_raw_buffer_load_b128(rw, v * 1024 + lane * 16, so, kStreamAux);
+    const int mo = B * 1024 + lane * Cfg::MPL;
+    if constexpr (Cfg::MPL == 2) {
+        s.meta[0] = __builtin_amdgcn_raw_buffer_load_b16(rw, mo, so, kStreamAux);
+    } else if constexpr (Cfg::MPL == 4) {
+        s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rw, mo, so, kStreamAux);
+    } else if constexpr (Cfg::MPL == 8) {
+        u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rw, mo, so, kStreamAux);
+        s.meta[0] = v.x;
+        s.meta[1] = v.y;
+    } else {
+        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, mo, so, kStreamAux);
+        s.meta[0] = v.x;
+        s.meta[1] = v.y;
+        s.meta[2] = v.z;
+        s.meta[3] = v.w;
+    }
+}
+
+// Lookups of one tile block; `tbase` is the LDS address of the tile's 32 tables, `sbase` of its group sums.
+template <int B, int GQ, bool HZ>
+__device__ __forceinline__ void consume_weights(const Stage<B, 1, GemvCfg<B, 1, GQ, HZ>::MPL>& s, uint32_t tbase,
+                                                uint32_t sbase, const uint32_t (&sel)[4], const float (&pw)[B],
+                                                float& y) {
+    using Cfg = GemvCfg<B, 1, GQ, HZ>;
+    constexpr uint32_t NIB = 0x1E1E1E1Eu;  // index * 2 bytes, one per byte
+    constexpr int TSTRIDE = 32;
+    constexpr int W = 4 * B;
+    constexpr int WPG = (GQ / 32) * B;
+    auto fetch = [&](int wi, _Float16 (&e)[8]) {
+        const int kb32 = wi / B, i = wi % B;
+        const int v = (kb32 * 32) / Cfg::CH;
+        const int ksub = ((kb32 * 32) % Cfg::CH) / 32;
+        const int tb = (kb32 * 8) * TSTRIDE;
+        const uint32_t w = word_of(s.c[v], ksub * B + i);
+        const uint32_t xe = (w << 1) & NIB;
+        const uint32_t xo = (w >> 3) & NIB;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            e[2 * k] = load_lds<_Float16>(index_into(xe, tbase, sel[k]) + (tb + (2 * k) * TSTRIDE));
+            e[2 * k + 1] = load_lds<_Float16>(index_into(xo, tbase, sel[k]) + (tb + (2 * k + 1) * TSTRIDE));
         }
-        return;
+    };
+    _Float16 e[2][8];
+    float a = 0.f;
+    fetch(0, e[0]);
+#pragma unroll
+    for (int wi = 0; wi < W; ++wi) {
+        if (wi + 1 < W) fetch(wi + 1, e[(wi + 1) & 1]);
+        if (wi % WPG == 0) a = 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a = fmaf(pw[wi % B], (float)e[wi & 1][u], a);
+        if (wi % WPG == WPG - 1) {
+            const int gi = wi / WPG;
+            const int mo = gi * Cfg::MSZ;
+            const uint32_t mw = s.meta[mo / 4];
+            const float sc = half_bits_to_float((mo % 4) ? (mw >> 16) : (mw & 0xffffu));
+            const float gs = load_lds<float>(sbase + gi * 4);
+            if constexpr (HZ) {
+                const float z = half_bits_to_float(mw >> 16);
+                y = fmaf(sc, fmaf(-z, gs, a), y);
+            } else {
+                y = fmaf(sc, fmaf(2.f, a, -gs), y);
+            }
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+template <int B, int GQ, bool HZ, bool SINGLE>
+__global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE> a) {
+    using Cfg = GemvCfg<B, 1, GQ, HZ>;
+    constexpr int D = Cfg::D;
+    constexpr int TPG = GQ / kLutGroup;  // tables per quantization group: 8, 16 or 32 consecutive lanes
+    __shared__ __attribute__((aligned(1024))) uint8_t tables[kGemvXSegmentTiles * kTableBytesPerKTile];
+    __shared__ float sums[kGemvXSegmentTiles * Cfg::GPT];
+    __shared__ float red[kWaves][kRows];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float pw[B];
+#pragma unroll
+    for (int i = 0; i < B; ++i) pw[i] = opaque((float)(1 << i));
+
+    const int g = SINGLE ? 0 : (int)blockIdx.y;
+    const GemvDesc& d = desc_of<SINGLE>(a, g);
+    const int n_seg = uniform(d.n_seg), n_ktiles = uniform(d.n_ktiles);
+    const int wg_local = (int)blockIdx.x;
+    if (wg_local >= uniform(d.n_row_blocks) * n_seg) return;
+    // (the division runs on the vector unit: bring its results back to scalar registers, or every buffer
+    // resource derived from them is taken for lane dependent)
+    const int rb = uniform(wg_local / n_seg), seg = uniform(wg_local % n_seg);
+    const int seg_tiles = uniform(d.seg_tiles);
+    const int k0 = seg * seg_tiles;
+    const int k1 = min(k0 + seg_tiles, n_ktiles);
+    const int per_wave = (k1 - k0 + kWaves - 1) / kWaves;
+    const int t0 = min(k0 + wave * per_wave, k1);
+    const int t1 = min(t0 + per_wave, k1);
+    Streams src;
+    src.w = uniform(d.tiles) + (size_t)rb * n_ktiles * Cfg::TB;
+    src.t = src.s = nullptr;
+    src.w_bytes = (uint32_t)(n_ktiles * Cfg::TB);
+    src.t_bytes = src.s_bytes = 0;
+
+    // first weight tiles on their way before anything else
+    Stage<B, 1, Cfg::MPL> st[D] = {};
+#pragma unroll
+    for (int s = 0; s < D; ++s) issue_weights<B, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
+
+    // tables and group sums of the segment: thread -> tables tid, tid + 256, ... (x beyond K reads as zero)
+    {
+        const rsrc_t rx = make_rsrc(uniform(d.lut_t), (uint32_t)uniform(d.K) * 2u);
+        const int n_tab = (k1 - k0) * kTablesPerKTile;
+        constexpr int kPasses = kGemvXSegmentTiles * kTablesPerKTile / (kWaves * 64);
+        static_assert(kPasses * kWaves * 64 == kGemvXSegmentTiles * kTablesPerKTile, "whole passes");
+        u32x2 xv[kPasses];
+#pragma unroll
+        for (int i = 0; i < kPasses; ++i)
+            xv[i] = __builtin_amdgcn_raw_buffer_load_b64(rx, (i * kWaves * 64 + tid) * 8, k0 * kKTile * 2, 0);
+        const uint32_t lt = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)tables));
+        const uint32_t ls = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<float>)sums));
+#pragma unroll
+        for (int i = 0; i < kPasses; ++i) {
+            const int j = i * kWaves * 64 + tid;
+            // (copy the elements out first: a bit cast applied directly to a vector element reads element 0)
+            const uint32_t w01 = xv[i].x, w23 = xv[i].y;
+            const half2_t x01 = __builtin_bit_cast(half2_t, w01), x23 = __builtin_bit_cast(half2_t, w23);
+            const float v[4] = {(float)x01[0], (float)x01[1], (float)x23[0], (float)x23[1]};
+            half8_t lo, hi;
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                float sum = 0.f;
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    if ((p >> t) & 1) sum += v[t];
+                if (p < 8) lo[p] = (_Float16)sum;
+                else hi[p - 8] = (_Float16)sum;
+            }
+            float gs = (v[0] + v[1]) + (v[2] + v[3]);
+#pragma unroll
+            for (int dlt = 1; dlt < TPG; dlt <<= 1) gs += __shfl_xor(gs, dlt, 64);
+            if (j < n_tab) {
+                store_lds<u32x4>(lt + j * 32, __builtin_bit_cast(u32x4, lo));
+                store_lds<u32x4>(lt + j * 32 + 16, __builtin_bit_cast(u32x4, hi));
+                if (j % TPG == 0) store_lds<float>(ls + (j / TPG) * 4, gs);
+            }
+        }
+    }
+    __syncthreads();
+
+    uint32_t sel[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) sel[k] = 0x03020100u | (uint32_t)(4 + k);
+    const uint32_t lt = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)tables));
+    const uint32_t ls = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<float>)sums));
+    float y = 0.f;
+    for (int base = t0; base < t1; base += D) {
+#pragma unroll
+        for (int s = 0; s < D; ++s) {
+            const int t = base + s;
+            if (t < t1) {
+                {
+                    const int rem = t1 - t;
+                    if (rem >= 7) __builtin_amdgcn_s_setprio(3);
+                    else if (rem >= 5) __builtin_amdgcn_s_setprio(2);
+                    else if (rem >= 3) __builtin_amdgcn_s_setprio(1);
+                    else __builtin_amdgcn_s_setprio(0);
+                }
+                consume_weights<B, GQ, HZ>(st[s], lt + (t - k0) * kTableBytesPerKTile, ls + (t - k0) * Cfg::GPT * 4, sel, pw, y);
+                issue_weights<B, GQ, HZ>(st[s], src, t + D < t1, t + D, lane);
+            }
+        }
     }
 
-    // K longer than one segment: publish this segment's partial sums and take a ticket
-    float* base_p = d.partial + (size_t)rb * n_seg * NP * kRows;
-    float* mine = base_p + (size_t)seg * NP * kRows;
-#pragma unroll
-    for (int n = 0; n < NP; ++n)
-        __hip_atomic_store(mine + n * kRows + lane, y[n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the partials have reached device-coherent memory
-    int32_t* ticket = d.tickets + rb;
-    int prev = 0;
-    if (lane == 0) prev = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    prev = __builtin_amdgcn_readfirstlane(prev);
-    if (prev != n_seg - 1) return;
-    // last ticket: every segment of this row block has been published; add them in segment order
-    float acc[NP];
-#pragma unroll
-    for (int n = 0; n < NP; ++n) acc[n] = 0.f;
-    for (int p0 = 0; p0 < n_seg; p0 += 4) {
-        float v[4][NP];
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int n = 0; n < NP; ++n)
-                v[q][n] = (p0 + q < n_seg) ? __hip_atomic_load(base_p + ((size_t)(p0 + q) * NP + n) * kRows + lane,
-                                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                           : 0.f;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int n = 0; n < NP; ++n) acc[n] += v[q][n];
-    }
-    if (m < M) {
-#pragma unroll
-        for (int n = 0; n < NP; ++n)
-            if (n < N) out[(size_t)n * M + m] = (_Float16)acc[n];
-    }
-    if (lane == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    red[wave][lane] = y;
+    __syncthreads();
+    if (wave != 0) return;
+    y = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    float yy[1] = {y};
+    finish_rows<1>(d, rb, seg, n_seg, lane, yy);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -530,6 +762,42 @@ int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc
     a.descs = descs_dev;
     a.n_gemv = n_gemv;
     return launch_format<false>(bits, has_zero, padded_tokens(N), group, a, max_workgroups, st);
+}
+
+template <int B, bool HZ, bool SINGLE>
+static int launch_x_group(int group, const KernelArgs<SINGLE>& a, int n_wg, hipStream_t st) {
+    const dim3 grid((unsigned)n_wg, (unsigned)a.n_gemv), block(kWaves * 64);
+    switch (group) {
+        case 32: hipLaunchKernelGGL((mpgemv_x_kernel<B, 32, HZ, SINGLE>), grid, block, 0, st, a); break;
+        case 64: hipLaunchKernelGGL((mpgemv_x_kernel<B, 64, HZ, SINGLE>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((mpgemv_x_kernel<B, 128, HZ, SINGLE>), grid, block, 0, st, a); break;
+    }
+    return launch_status();
+}
+
+template <bool SINGLE>
+static int launch_x_format(int bits, int has_zero, int group, const KernelArgs<SINGLE>& a, int n_wg, hipStream_t st) {
+    if (bits == 1) {
+        return has_zero ? launch_x_group<1, true, SINGLE>(group, a, n_wg, st)
+                        : launch_x_group<1, false, SINGLE>(group, a, n_wg, st);
+    }
+    if (bits == 2) return launch_x_group<2, true, SINGLE>(group, a, n_wg, st);
+    return launch_x_group<4, true, SINGLE>(group, a, n_wg, st);
+}
+
+int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y, void* workspace, hipStream_t st) {
+    KernelArgs<true> a;
+    fill_desc_x(a.single, L, packed, x, y, workspace);
+    a.n_gemv = 1;
+    return launch_x_format<true>(L.bits, L.has_zero, L.group, a, plan_gemv_x(L).n_workgroups, st);
+}
+
+int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
+                          hipStream_t st) {
+    KernelArgs<false> a;
+    a.descs = descs_dev;
+    a.n_gemv = n_gemv;
+    return launch_x_format<false>(bits, has_zero, group, a, max_workgroups, st);
 }
 
 // copies up to 16 descriptors per launch from the kernel arguments into the device table

@@ -63,6 +63,16 @@ def mpgemv(shape, blob, x, workspace=None):
     return y.cpu().numpy()
 
 
+def mpgemv_x(shape, blob, x, workspace=None):
+    """One token through the kernel that builds its tables itself; x numpy/torch fp16 [1][K] or [K]."""
+    xd = x if torch.is_tensor(x) else to_dev(x)
+    ws = gemv_workspace(shape, 1) if workspace is None else workspace
+    y = torch.full((1, shape.M), float("nan"), dtype=torch.float16, device=dev())
+    tman.tman_mpgemv_x(shape, blob, xd, y, ws)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
 def mpgemm(shape, blob, x):
     xd = x if torch.is_tensor(x) else to_dev(x)
     N = xd.shape[0]

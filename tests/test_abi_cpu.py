@@ -85,6 +85,7 @@ def test_bad_shapes_are_rejected_everywhere(lib, shape, status):
     assert lib.tman_pack_weights(C.byref(shape), FAKE, FAKE, FAKE, FAKE, None) == status
     assert lib.tman_unpack_weights(C.byref(shape), FAKE, FAKE, None, None, None) == status
     assert lib.tman_mpgemv(C.byref(shape), FAKE, FAKE, 1, FAKE, FAKE, 1 << 30, None) == status
+    assert lib.tman_mpgemv_x(C.byref(shape), FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == status
     assert lib.tman_mpgemm(C.byref(shape), FAKE, FAKE, 1, FAKE, None, 0, None) == status
 
 
@@ -181,6 +182,45 @@ def test_batched_gemv_rejects_bad_arguments(lib):
     assert lib.tman_mpgemv_batch_run(0, shapes, 1, FAKE, None) == -4
     assert lib.tman_mpgemv_batch_run(2, shapes, 9, FAKE, None) == -4
     assert lib.tman_mpgemv_batch_run(2, mixed, 1, FAKE, None) == -4
+
+
+def test_one_token_gemv_with_own_tables_rejects_bad_arguments(lib):
+    s = _shape()
+    need = lib.tman_mpgemv_workspace_bytes(C.byref(s), 1)
+    assert lib.tman_mpgemv_x(None, FAKE, FAKE, FAKE, FAKE, need, None) == -1
+    assert lib.tman_mpgemv_x(C.byref(s), None, FAKE, FAKE, FAKE, need, None) == -1
+    assert lib.tman_mpgemv_x(C.byref(s), FAKE, None, FAKE, FAKE, need, None) == -1
+    assert lib.tman_mpgemv_x(C.byref(s), FAKE, FAKE, None, FAKE, need, None) == -1
+    assert lib.tman_mpgemv_x(C.byref(s), FAKE, FAKE, FAKE, None, 0, None) == -5
+    assert lib.tman_mpgemv_x(C.byref(s), FAKE, FAKE, FAKE, FAKE, need - 1, None) == -5
+    assert lib.tman_mpgemv_x(C.byref(s), FAKE, FAKE + 2, FAKE, FAKE, need, None) == -6  # x: 16-byte aligned
+    assert lib.tman_mpgemv_x(C.byref(s), FAKE + 8, FAKE, FAKE, FAKE, need, None) == -6
+
+    shapes = (api._CShape * 2)(_shape(M=64, K=256), _shape(M=128, K=512))
+    packed, xs, y = _ptrs(FAKE, FAKE), _ptrs(FAKE, FAKE), _ptrs(FAKE, FAKE)
+    ws = _ptrs(FAKE, FAKE + 0x10000)
+    needs = [lib.tman_mpgemv_workspace_bytes(C.byref(shapes[i]), 1) for i in range(2)]
+    wsb = (C.c_size_t * 2)(*needs)
+
+    def prepare(count=2, shapes=shapes, packed=packed, xs=xs, y=y, ws=ws, wsb=wsb, desc=FAKE):
+        return lib.tman_mpgemv_x_batch_prepare(count, shapes, packed, xs, y, ws, wsb, desc, None)
+
+    assert prepare(shapes=None) == -1
+    assert prepare(count=0) == -4 and prepare(count=257) == -4
+    assert prepare(packed=None) == -1 and prepare(xs=None) == -1 and prepare(y=None) == -1
+    assert prepare(ws=None) == -1 and prepare(wsb=None) == -1 and prepare(desc=None) == -1
+    assert prepare(desc=FAKE + 4) == -6
+    assert prepare(xs=_ptrs(FAKE, None)) == -1
+    assert prepare(xs=_ptrs(FAKE, FAKE + 2)) == -6
+    assert prepare(wsb=(C.c_size_t * 2)(needs[0], needs[1] - 1)) == -5
+    assert prepare(ws=_ptrs(FAKE, FAKE)) == -5
+    mixed = (api._CShape * 2)(_shape(M=64, K=256, bits=4), _shape(M=128, K=512, bits=2))
+    assert prepare(shapes=mixed) == -4
+    assert lib.tman_mpgemv_x_batch_run(2, None, FAKE, None) == -1
+    assert lib.tman_mpgemv_x_batch_run(2, shapes, None, None) == -1
+    assert lib.tman_mpgemv_x_batch_run(2, shapes, FAKE + 8, None) == -6
+    assert lib.tman_mpgemv_x_batch_run(0, shapes, FAKE, None) == -4
+    assert lib.tman_mpgemv_x_batch_run(2, mixed, FAKE, None) == -4
 
 
 def test_prefill_tile_rows_query(lib):
