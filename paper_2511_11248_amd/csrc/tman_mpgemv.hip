@@ -505,8 +505,8 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
 // to three or four other workgroups.  The workgroup builds them itself from the activations of its
 // segment (6 KB) while its first weight tiles are on their way, so a decode step needs no launch for
 // the table precompute, no table traffic between the two kernels, and no per-tile copy of a table
-// slice into LDS.  The entries are computed exactly as build_lut_kernel computes them (fp32 sums in
-// ascending order, one rounding to fp16), as are the group sums (same butterfly).
+// slice into LDS.  The entries have the values build_lut_kernel computes (fp32 sums in ascending order,
+// one rounding to fp16), as have the group sums (same tree of additions).
 //
 // A lookup address is tile base | index byte: one v_perm_b32 takes byte k of the prepared index word as
 // byte 0 and bytes 1..3 of the tile's table base (a multiple of 1024), the table's place inside the
@@ -516,6 +516,24 @@ __device__ __forceinline__ uint32_t index_into(uint32_t idx_word, uint32_t base,
     uint32_t r;
     asm("v_perm_b32 %0, %1, %2, %3" : "=v"(r) : "v"(idx_word), "v"(base), "s"(selector));
     return r;
+}
+
+// Sum over blocks of W consecutive lanes (W = 8, 16 or 32), every lane of a block receiving the block's sum.
+// A butterfly: at each step a lane adds the sum of the neighbouring sub-block, which all lanes of that
+// sub-block hold, so the mirror permutations of DPP serve as well as an exchange with lane ^ d.
+template <int CTRL>
+__device__ __forceinline__ float add_dpp(float v) {
+    return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <int W>
+__device__ __forceinline__ float sum_over_lanes(float v) {
+    v = add_dpp<0xB1>(v);   // quad_perm [1,0,3,2]: lane ^ 1
+    v = add_dpp<0x4E>(v);   // quad_perm [2,3,0,1]: lane ^ 2
+    v = add_dpp<0x141>(v);  // row_half_mirror: the other quad of 8 lanes
+    if constexpr (W >= 16) v = add_dpp<0x140>(v);  // row_mirror: the other half of 16 lanes
+    if constexpr (W >= 32)  // lane ^ 16 (crosses DPP rows)
+        v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
+    return v;
 }
 
 template <int B, int GQ, bool HZ>
@@ -654,19 +672,23 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
             const uint32_t w01 = xv[i].x, w23 = xv[i].y;
             const half2_t x01 = __builtin_bit_cast(half2_t, w01), x23 = __builtin_bit_cast(half2_t, w23);
             const float v[4] = {(float)x01[0], (float)x01[1], (float)x23[0], (float)x23[1]};
+            // entry p = sum of the v[t] with bit t of p set, added in ascending t
+            float e[16];
+            e[0] = 0.f;
+            e[1] = v[0];
+            e[2] = v[1];
+            e[3] = v[0] + v[1];
+#pragma unroll
+            for (int p = 4; p < 8; ++p) e[p] = p == 4 ? v[2] : e[p - 4] + v[2];
+#pragma unroll
+            for (int p = 8; p < 16; ++p) e[p] = p == 8 ? v[3] : e[p - 8] + v[3];
             half8_t lo, hi;
 #pragma unroll
-            for (int p = 0; p < 16; ++p) {
-                float sum = 0.f;
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if ((p >> t) & 1) sum += v[t];
-                if (p < 8) lo[p] = (_Float16)sum;
-                else hi[p - 8] = (_Float16)sum;
+            for (int p = 0; p < 8; ++p) {
+                lo[p] = (_Float16)e[p];
+                hi[p] = (_Float16)e[p + 8];
             }
-            float gs = (v[0] + v[1]) + (v[2] + v[3]);
-#pragma unroll
-            for (int dlt = 1; dlt < TPG; dlt <<= 1) gs += __shfl_xor(gs, dlt, 64);
+            const float gs = sum_over_lanes<TPG>((v[0] + v[1]) + (v[2] + v[3]));
             if (j < n_tab) {
                 store_lds<u32x4>(lt + j * 32, __builtin_bit_cast(u32x4, lo));
                 store_lds<u32x4>(lt + j * 32 + 16, __builtin_bit_cast(u32x4, hi));
