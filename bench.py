@@ -33,7 +33,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # WRITE_SIZE runs of this script scaled by a plain copy of known size (--calibration-copy); the counters
 # cannot be read from inside the process.  Source: profiles/mpgemv_7b_w2g64_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    ("mpgemv_x", "7b_w2g64", 1): 63_915_008 + 525_517,
+    ("mpgemv_x", "7b_w2g64", 1): 63_912_960 + 525_517,
     ("mpgemm", "prefill_w4g64", 1024): 92_630_221 + 22_544_384,
 }
 
@@ -49,9 +49,12 @@ def parse():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--event-every", type=int, default=8,
+    ap.add_argument("--event-every", type=int, default=20,
                     help="bracket every n-th launch of the dominant kernel with HIP events (each pair costs a few "
                          "microseconds of stream time, which would otherwise dominate a 20 us step)")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the context figures (cache-resident, two-launch, device copy): under a profiler the "
+                         "kernel statistics then cover the timed, cache-cold launches only")
     ap.add_argument("--table", action="store_true",
                     help="instead of the headline line: time every configuration (decode workloads at their token "
                          "counts, prefill at 256/1024/2048 tokens), check each against the CPU oracle, and print a table")
@@ -198,6 +201,42 @@ def run_table(args, torch, tman, synth, dev):
               f"{err:.2e} (every 8th row)", f"{cpu_t * 1e3:.0f} (8 x the sampled rows)", used, f"{cpu_t / sec:.0f}x"])
 
 
+def context_figures(args, torch, dev, job, n_inst):
+    """The step on one copy of the layer set (cache-resident), as two launches, and a plain device copy."""
+    x_calls, lut_calls, gemv_calls, stream = job["x_calls"], job["lut_calls"], job["gemv_calls"], job["stream"]
+    weight_bytes_per_step = job["weight_bytes_per_step"]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        x_calls[0](stream)
+    torch.cuda.synchronize()
+    hot_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
+    # the same step as two launches (table precompute kernel, then the lookup kernel reading its tables)
+    for i in range(args.warmup):
+        lut_calls[i % n_inst](stream)
+        gemv_calls[i % n_inst](stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        lut_calls[i % n_inst](stream)
+        gemv_calls[i % n_inst](stream)
+    torch.cuda.synchronize()
+    two_launch_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
+    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cp_dst = torch.empty_like(cp_src)
+    cp_dst.copy_(cp_src)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        cp_dst.copy_(cp_src)
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2.0 * (1 << 30) / (time.perf_counter() - t0) / 1e9
+    del cp_src, cp_dst
+
+    return {"cache_resident_GBs": round(hot_value, 1), "two_launch_step_GBs": round(two_launch_value, 1),
+            "device_copy_GBs_read_plus_write": round(copy_gbs, 1)}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -274,34 +313,10 @@ def main():
 
     # context figures (not the headline): the same step on ONE copy of the layer set (63 MB: served by the
     # 256 MB Infinity Cache), the bit-plane bytes alone, and what a plain device copy moves on this machine
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        x_calls[0](stream)
-    torch.cuda.synchronize()
-    hot_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
-    # the same step as two launches (table precompute kernel, then the lookup kernel reading its tables)
-    for i in range(args.warmup):
-        lut_calls[i % n_inst](stream)
-        gemv_calls[i % n_inst](stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        lut_calls[i % n_inst](stream)
-        gemv_calls[i % n_inst](stream)
-    torch.cuda.synchronize()
-    two_launch_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
     codes_bytes = sum(s.M * s.K * w.bits // 8 for s in shapes)
-    cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    cp_dst = torch.empty_like(cp_src)
-    cp_dst.copy_(cp_src)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(5):
-        cp_dst.copy_(cp_src)
-    torch.cuda.synchronize()
-    copy_gbs = 5 * 2.0 * (1 << 30) / (time.perf_counter() - t0) / 1e9
-    del cp_src, cp_dst
+    context = {}
+    if not args.no_context:
+        context = context_figures(args, torch, dev, job, n_inst)
 
     out = {
         "metric": "decode mpGEMV weight GB/s", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
@@ -312,10 +327,7 @@ def main():
                                f"step = one launch: every workgroup builds the lookup tables of its K segment "
                                f"from the {len(acts)} activations, then does its lookups",
                    "weight_bytes_per_step": int(weight_bytes_per_step), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-                   "codes_only_GBs": round(value * codes_bytes / weight_bytes_per_step, 1),
-                   "cache_resident_GBs": round(hot_value, 1),
-                   "two_launch_step_GBs": round(two_launch_value, 1),
-                   "device_copy_GBs_read_plus_write": round(copy_gbs, 1)},
+                   "codes_only_GBs": round(value * codes_bytes / weight_bytes_per_step, 1), **context},
         "roofline": roofline,
     }
 
