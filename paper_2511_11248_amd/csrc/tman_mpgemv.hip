@@ -215,15 +215,14 @@ struct Streams {
     uint32_t w_bytes, t_bytes, s_bytes;
 };
 
-// Requests tile kt.  With `live` false nothing is fetched and the stage reads as zeros: the caller
-// needs no branch around the request, so a tile's lookups and the next request stay one basic block.
+// Requests the weights of tile kt: bit-plane chunks and group parameters of the lane's row.  With `live`
+// false nothing is fetched and the stage reads as zeros: the caller needs no branch around the request, so
+// a tile's lookups and the next request stay one basic block.
 template <int B, int NP, int GQ, bool HZ>
-__device__ __forceinline__ void issue_tile(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, const Streams& src, bool live,
-                                           int kt, int lane) {
+__device__ __forceinline__ void issue_weights(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, const Streams& src, bool live,
+                                              int kt, int lane) {
     using Cfg = GemvCfg<B, NP, GQ, HZ>;
     const rsrc_t rw = make_rsrc(src.w, live ? src.w_bytes : 0u);
-    const rsrc_t rt = make_rsrc(src.t, live ? src.t_bytes : 0u);
-    const rsrc_t rs = make_rsrc(src.s, live ? src.s_bytes : 0u);
     const int so = kt * Cfg::TB;  // scalar offset of the tile block inside the row block
 #pragma unroll
     for (int v = 0; v < B; ++v) s.c[v] = __builtin_amdgcn_raw_buffer_load_b128(rw, v * 1024 + lane * 16, so, kStreamAux);
@@ -243,6 +242,16 @@ __device__ __forceinline__ void issue_tile(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::
         s.meta[2] = v.z;
         s.meta[3] = v.w;
     }
+}
+
+// Requests tile kt: its weights, its slice of the lookup tables and its group sums (same rule for `live`).
+template <int B, int NP, int GQ, bool HZ>
+__device__ __forceinline__ void issue_tile(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, const Streams& src, bool live,
+                                           int kt, int lane) {
+    using Cfg = GemvCfg<B, NP, GQ, HZ>;
+    issue_weights<B, NP, GQ, HZ>(s, src, live, kt, lane);
+    const rsrc_t rt = make_rsrc(src.t, live ? src.t_bytes : 0u);
+    const rsrc_t rs = make_rsrc(src.s, live ? src.s_bytes : 0u);
     const int to = kt * Cfg::T_BYTES;
 #pragma unroll
     for (int q = 0; q < NP; ++q) s.tt[q] = __builtin_amdgcn_raw_buffer_load_b128(rt, q * 1024 + lane * 16, to, 0);
@@ -536,32 +545,6 @@ __device__ __forceinline__ float sum_over_lanes(float v) {
     return v;
 }
 
-template <int B, int GQ, bool HZ>
-__device__ __forceinline__ void issue_weights(Stage<B, 1, GemvCfg<B, 1, GQ, HZ>::MPL>& s, const Streams& src, bool live,
-                                              int kt, int lane) {
-    using Cfg = GemvCfg<B, 1, GQ, HZ>;
-    const rsrc_t rw = make_rsrc(src.w, live ? src.w_bytes : 0u);
-    const int so = kt * Cfg::TB;
-#pragma unroll
-    for (int v = 0; v < B; ++v) s.c[v] = __builtin_amdgcn_raw_buffer_load_b128(rw, v * 1024 + lane * 16, so, kStreamAux);
-    const int mo = B * 1024 + lane * Cfg::MPL;
-    if constexpr (Cfg::MPL == 2) {
-        s.meta[0] = __builtin_amdgcn_raw_buffer_load_b16(rw, mo, so, kStreamAux);
-    } else if constexpr (Cfg::MPL == 4) {
-        s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rw, mo, so, kStreamAux);
-    } else if constexpr (Cfg::MPL == 8) {
-        u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rw, mo, so, kStreamAux);
-        s.meta[0] = v.x;
-        s.meta[1] = v.y;
-    } else {
-        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, mo, so, kStreamAux);
-        s.meta[0] = v.x;
-        s.meta[1] = v.y;
-        s.meta[2] = v.z;
-        s.meta[3] = v.w;
-    }
-}
-
 // Lookups of one tile block; `tbase` is the LDS address of the tile's 32 tables, `sbase` of its group sums.
 template <int B, int GQ, bool HZ>
 __device__ __forceinline__ void consume_weights(const Stage<B, 1, GemvCfg<B, 1, GQ, HZ>::MPL>& s, uint32_t tbase,
@@ -651,7 +634,7 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
     // first weight tiles on their way before anything else
     Stage<B, 1, Cfg::MPL> st[D] = {};
 #pragma unroll
-    for (int s = 0; s < D; ++s) issue_weights<B, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
+    for (int s = 0; s < D; ++s) issue_weights<B, 1, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
 
     // tables and group sums of the segment: thread -> tables tid, tid + 256, ... (x beyond K reads as zero)
     {
@@ -717,7 +700,7 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
                     else __builtin_amdgcn_s_setprio(0);
                 }
                 consume_weights<B, GQ, HZ>(st[s], lt + (t - k0) * kTableBytesPerKTile, ls + (t - k0) * Cfg::GPT * 4, sel, pw, y);
-                issue_weights<B, GQ, HZ>(st[s], src, t + D < t1, t + D, lane);
+                issue_weights<B, 1, GQ, HZ>(st[s], src, t + D < t1, t + D, lane);
             }
         }
     }
