@@ -209,3 +209,24 @@ def test_batch_of_mixed_small_shapes(oracle_lib):
         assert oracle.row_relative_error(y.cpu().numpy(), Y).max() <= TOL
         single = mpgemv(shape, blob, x)
         assert np.array_equal(single.view(np.uint16), y.cpu().numpy().view(np.uint16))  # same schedule, same bits
+
+
+def test_largest_batch(oracle_lib):
+    """TMAN_MAX_BATCH = 256 GEMVs in one launch, small ragged shapes, three tokens, every output checked."""
+    N, bits, group, count = 3, 4, 32, 256
+    shapes, blobs, luts, ys, wss, refs = [], [], [], [], [], []
+    for i in range(count):
+        M, K = 40 + (i * 41) % 140, 32 * (1 + i % 7)  # enough rows for the row-normalised metric
+        q, s, z, x = rand_case(15000 + i, M, K, N, bits, group)
+        shape = tman.Shape(M, K, bits, group)
+        lut = torch.empty(tman.tman_lut_bytes(N, K, group), dtype=torch.uint8, device=dev())
+        tman.tman_build_lut(to_dev(x), N, K, group, lut)
+        shapes.append(shape); blobs.append(pack(shape, q, s, z)); luts.append(lut)
+        ys.append(torch.full((N, M), float("nan"), dtype=torch.float16, device=dev()))
+        wss.append(gemv_workspace(shape, N)); refs.append((q, s, z, x))
+    desc = torch.empty(tman.tman_mpgemv_batch_desc_bytes(count), dtype=torch.uint8, device=dev())
+    tman.tman_mpgemv_batch_prepare(shapes, blobs, luts, N, ys, wss, desc)
+    tman.tman_mpgemv_batch_run(shapes, N, desc)
+    torch.cuda.synchronize()
+    for y, (q, s, z, x) in zip(ys, refs):
+        assert oracle.row_relative_error(y.cpu().numpy(), oracle.matmul(q, s, z, x, bits, group)).max() <= TOL

@@ -150,3 +150,23 @@ def test_batch_of_mixed_small_shapes(oracle_lib):
     for shape, y, blob, (q, s, z, x) in zip(shapes, ys, blobs, refs):
         assert oracle.row_relative_error(y.cpu().numpy(), oracle.matmul(q, s, z, x, bits, group)).max() <= TOL
         assert np.array_equal(mpgemv_x(shape, blob, x).view(np.uint16), y.cpu().numpy().view(np.uint16))
+
+
+def test_largest_batch(oracle_lib):
+    """TMAN_MAX_BATCH = 256 GEMVs in one launch (more than one descriptor chunk, a grid of 256 rows of
+    workgroups), small ragged shapes, every output checked."""
+    bits, group, count = 2, 32, 256
+    shapes, blobs, xs, ys, wss, refs = [], [], [], [], [], []
+    for i in range(count):
+        M, K = 40 + (i * 37) % 150, 32 * (1 + i % 9)  # enough rows for the row-normalised metric
+        q, s, z, x = rand_case(12000 + i, M, K, 1, bits, group)
+        shape = tman.Shape(M, K, bits, group)
+        shapes.append(shape); blobs.append(pack(shape, q, s, z)); xs.append(to_dev(x))
+        ys.append(torch.full((1, M), float("nan"), dtype=torch.float16, device=dev()))
+        wss.append(gemv_workspace(shape, 1)); refs.append((q, s, z, x))
+    desc = torch.empty(tman.tman_mpgemv_batch_desc_bytes(count), dtype=torch.uint8, device=dev())
+    tman.tman_mpgemv_x_batch_prepare(shapes, blobs, xs, ys, wss, desc)
+    tman.tman_mpgemv_x_batch_run(shapes, desc)
+    torch.cuda.synchronize()
+    for y, (q, s, z, x) in zip(ys, refs):
+        assert oracle.row_relative_error(y.cpu().numpy(), oracle.matmul(q, s, z, x, bits, group)).max() <= TOL
