@@ -68,6 +68,7 @@ constexpr int kGemvSegmentTiles = TMAN_SEG;
 #else
 constexpr int kGemvSegmentTiles = 32;
 #endif
+constexpr int kGemvManyTokensSegmentTiles = 24;  // for 4 or 8 tokens
 
 // One GEMV of a decode launch, as the kernel sees it.
 struct GemvDesc {

@@ -57,8 +57,8 @@ static GemvPlan plan_segments(const Layout& L, int np, int max_seg) {
 
 GemvPlan plan_gemv(const Layout& L, int N) {
     const int np = padded_tokens(N);
-    // with four or eight tokens a tile takes 2 - 3 times as long: shorter segments, more workgroups (measured)
-    return plan_segments(L, np, np >= 4 ? kGemvSegmentTiles / 2 : kGemvSegmentTiles);
+    // with four or eight tokens a tile takes about twice as long: shorter segments, more workgroups (measured)
+    return plan_segments(L, np, np >= 4 ? kGemvManyTokensSegmentTiles : kGemvSegmentTiles);
 }
 
 GemvPlan plan_gemv_x(const Layout& L) { return plan_segments(L, 1, kGemvXSegmentTiles); }
@@ -267,15 +267,68 @@ template <> struct EntryT<2> { typedef half2_t type; };
 template <> struct EntryT<4> { typedef half4_t type; };
 template <> struct EntryT<8> { typedef half8_t type; };
 
-template <int NP>
-__device__ __forceinline__ void accumulate(const typename EntryT<NP>::type& e, float pw, float (&a)[NP]) {
-    if constexpr (NP == 1) {
-        a[0] = fmaf(pw, (float)e, a[0]);
-    } else {
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+// Plane weights 2^i ("shift and accumulate") in the two forms the accumulation uses.
+//
+// One or two tokens: a uniform float, the entry is added with a mixed-precision FMA.
+// Four or eight tokens: a lookup returns the entries of 4 (8) tokens for the lane's row, and adding them with
+// one FMA per token makes the kernel bound by vector instruction issue.  The matrix pipe does the same
+// additions in one 4x4x4 MFMA per four tokens: with the 64 lanes as 16 blocks of 4, lane (b, j) supplies as
+// B[k][j] its own four entries (k = token) and as A[i][k] row i = j of 2^plane times the identity, so
+// D[i][j] = 2^plane * (entry of token i in lane (b, j)): register i of the lane's accumulator is token i of
+// its own row.  fp16 inputs, exact products, fp32 accumulation, as with the FMA.
+template <int B, int NP>
+struct PlaneWeights {
+    float pw[B];
+    half4_t hot[B];  // NP >= 4: row (lane % 4) of 2^i * identity
+};
+
+template <int B, int NP>
+__device__ __forceinline__ PlaneWeights<B, NP> make_plane_weights(int lane) {
+    PlaneWeights<B, NP> w;
 #pragma unroll
-        for (int n = 0; n < NP; ++n) a[n] = fmaf(pw, (float)e[n], a[n]);
+    for (int i = 0; i < B; ++i) {
+        w.pw[i] = opaque((float)(1 << i));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w.hot[i][k] = (lane & 3) == k ? (_Float16)(float)(1 << i) : (_Float16)0.f;
     }
+    return w;
 }
+
+template <int NP>
+struct Accum {
+    float a[NP < 4 ? NP : 1];
+    float4_t q[NP >= 4 ? NP / 4 : 1];
+    __device__ __forceinline__ void clear() {
+        if constexpr (NP < 4) {
+#pragma unroll
+            for (int n = 0; n < NP; ++n) a[n] = 0.f;
+        } else {
+#pragma unroll
+            for (int h = 0; h < NP / 4; ++h) q[h] = float4_t{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+    template <int B>
+    __device__ __forceinline__ void add(const typename EntryT<NP>::type& e, const PlaneWeights<B, NP>& w, int plane) {
+        if constexpr (NP == 1) {
+            a[0] = fmaf(w.pw[plane], (float)e, a[0]);
+        } else if constexpr (NP == 2) {
+#pragma unroll
+            for (int n = 0; n < NP; ++n) a[n] = fmaf(w.pw[plane], (float)e[n], a[n]);
+        } else if constexpr (NP == 4) {
+            q[0] = __builtin_amdgcn_mfma_f32_4x4x4f16(w.hot[plane], e, q[0], 0, 0, 0);
+        } else {
+            const half4_t lo = {e[0], e[1], e[2], e[3]}, hi = {e[4], e[5], e[6], e[7]};
+            q[0] = __builtin_amdgcn_mfma_f32_4x4x4f16(w.hot[plane], lo, q[0], 0, 0, 0);
+            q[1] = __builtin_amdgcn_mfma_f32_4x4x4f16(w.hot[plane], hi, q[1], 0, 0, 0);
+        }
+    }
+    __device__ __forceinline__ float get(int n) const {
+        if constexpr (NP < 4) return a[n];
+        else return q[n / 4][n % 4];
+    }
+};
 
 // Lookups of one tile block for the lane's row.  `lds` is the LDS address of the wave's private slot;
 // the callers make it a link-time constant (one copy of the code per wave of the workgroup), so it
@@ -285,7 +338,7 @@ __device__ __forceinline__ void accumulate(const typename EntryT<NP>::type& e, f
 // results of word w are accumulated, so LDS latency overlaps the arithmetic with few live registers.
 template <int B, int NP, int GQ, bool HZ>
 __device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, uint32_t lds, int lane,
-                                             const float (&pw)[B], float (&y)[NP]) {
+                                             const PlaneWeights<B, NP>& pw, float (&y)[NP]) {
     using Cfg = GemvCfg<B, NP, GQ, HZ>;
     typedef typename EntryT<NP>::type entry_t;
     constexpr int EB = 2 * NP;                                       // bytes per table entry
@@ -324,17 +377,14 @@ __device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, G
     };
 
     entry_t e[2][8];
-    float a[NP];
+    Accum<NP> a;
     fetch(0, e[0]);
 #pragma unroll
     for (int wi = 0; wi < W; ++wi) {
         if (wi + 1 < W) fetch(wi + 1, e[(wi + 1) & 1]);
-        if (wi % WPG == 0) {
+        if (wi % WPG == 0) a.clear();
 #pragma unroll
-            for (int n = 0; n < NP; ++n) a[n] = 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) accumulate<NP>(e[wi & 1][u], pw[wi % B], a);
+        for (int u = 0; u < 8; ++u) a.template add<B>(e[wi & 1][u], pw, wi % B);
         if (wi % WPG == WPG - 1) {
             // scale and zero of the quantization block just finished
             const int gi = wi / WPG;
@@ -345,10 +395,10 @@ __device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, G
             if constexpr (HZ) {
                 const float z = half_bits_to_float(mw >> 16);  // 4-byte entry: scale low, zero high
 #pragma unroll
-                for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(-z, load_lds<float>(sg + n * 4), a[n]), y[n]);
+                for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(-z, load_lds<float>(sg + n * 4), a.get(n)), y[n]);
             } else {
 #pragma unroll
-                for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(2.f, a[n], -load_lds<float>(sg + n * 4)), y[n]);
+                for (int n = 0; n < NP; ++n) y[n] = fmaf(sc, fmaf(2.f, a.get(n), -load_lds<float>(sg + n * 4)), y[n]);
             }
         }
         // keep the pipeline order, which bounds the live registers: the first stops the compiler from
@@ -430,9 +480,7 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    float pw[B];  // plane weights 2^i: "shift and accumulate"
-#pragma unroll
-    for (int i = 0; i < B; ++i) pw[i] = opaque((float)(1 << i));
+    const PlaneWeights<B, NP> pw = make_plane_weights<B, NP>(lane);
 
     // The grid is (workgroups of the largest GEMV) x (GEMVs): a workgroup knows its GEMV from its block
     // index, without searching the descriptor table (every workgroup of a launch starts at the same time,
