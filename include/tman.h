@@ -148,7 +148,7 @@ int tman_mpgemv_batch_run(int32_t count, const tman_shape_t *shapes, int32_t N, 
  * Decoding mpGEMV of ONE token with the table precompute inside the lookup kernel (Sec. 2.2, Sec. 4.3 for
  * the lookups; Sec. 5 moves the precompute into a kernel of its own because it is costly on the paper's
  * hardware, whereas here a kernel boundary costs more than the precompute).  Every workgroup builds the
- * tables of its own K segment (at most 3072 columns: 768 tables, 24 KB) in LDS from the activations,
+ * tables of its own K segment (at most 4096 columns: 1024 tables, 32 KB) in LDS from the activations,
  * exactly as tman_build_lut computes them (fp32 sums in ascending order, one rounding to fp16; the same
  * group sums), and then performs the same lookups as tman_mpgemv.  The result is what
  * tman_build_lut + tman_mpgemv give for N = 1, up to the order of the fp32 additions across K.

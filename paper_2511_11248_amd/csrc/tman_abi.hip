@@ -188,13 +188,14 @@ int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t* shapes, const voi
     if (rc != TMAN_OK) return rc;
     if (!desc) return TMAN_ERR_NULL;
     if (!aligned16(desc)) return TMAN_ERR_ALIGN;
-    int max_wg = 0;
+    int max_wg = 0, max_seg_tiles = 0;  // grid = (workgroups of the largest GEMV) x count; LDS for the longest segment
     for (int i = 0; i < count; ++i) {
-        const int n = plan_gemv_x(make_layout(&shapes[i])).n_workgroups;
-        if (n > max_wg) max_wg = n;
+        const GemvPlan p = plan_gemv_x(make_layout(&shapes[i]));
+        if (p.n_workgroups > max_wg) max_wg = p.n_workgroups;
+        if (p.seg_tiles > max_seg_tiles) max_seg_tiles = p.seg_tiles;
     }
     return launch_mpgemv_x_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO,
-                                 static_cast<const GemvDesc*>(desc), count, max_wg, (hipStream_t)stream);
+                                 static_cast<const GemvDesc*>(desc), count, max_wg, max_seg_tiles, (hipStream_t)stream);
 }
 
 int32_t tman_mpgemm_tile_rows(const tman_shape_t* shape, int32_t N) {

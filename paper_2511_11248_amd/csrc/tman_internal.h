@@ -92,9 +92,10 @@ struct GemvPlan {
     size_t partial_bytes;
 };
 GemvPlan plan_gemv(const Layout& L, int N);
-// Plan of the one-token kernel that builds its tables itself: shorter segments (less LDS for the
-// tables of a segment, more workgroups; measured).
-constexpr int kGemvXSegmentTiles = 24;
+// Plan of the one-token kernel that builds its tables itself: at most 32 tiles per segment (32 KB of tables
+// in LDS), 24 when K has to be cut anyway.
+constexpr int kGemvXSegmentTiles = 32;
+constexpr int kGemvXLongSegmentTiles = 24;
 GemvPlan plan_gemv_x(const Layout& L);
 void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
                int wg_begin);
@@ -114,7 +115,7 @@ int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc
 void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x, void* y, void* workspace);
 int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y, void* workspace, hipStream_t st);
 int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
-                          hipStream_t st);
+                          int max_seg_tiles, hipStream_t st);
 int launch_write_descs(const GemvDesc* host, int count, GemvDesc* dev, hipStream_t st);
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);
 int mpgemm_row_blocks_per_workgroup(const Layout& L, int N);

@@ -61,7 +61,14 @@ GemvPlan plan_gemv(const Layout& L, int N) {
     return plan_segments(L, np, np >= 4 ? kGemvManyTokensSegmentTiles : kGemvSegmentTiles);
 }
 
-GemvPlan plan_gemv_x(const Layout& L) { return plan_segments(L, 1, kGemvXSegmentTiles); }
+// Segments of the kernel that builds its own tables (measured on the 7B and 3.8B layer sets): a K that one
+// workgroup can take whole - up to 32 tiles and about 80 KB of packed weights per row block - is one segment,
+// which spares the exchange of partial sums; a longer K is cut into segments of at most 24 tiles.
+GemvPlan plan_gemv_x(const Layout& L) {
+    int whole = 81920 / L.tile_bytes;
+    if (whole > kGemvXSegmentTiles) whole = kGemvXSegmentTiles;
+    return plan_segments(L, 1, L.n_ktiles <= whole ? whole : kGemvXLongSegmentTiles);
+}
 
 static void fill_desc_plan(GemvDesc& d, const Layout& L, const GemvPlan& p, const void* packed, const void* lut, int N,
                            void* y, void* workspace, int wg_begin) {
@@ -558,9 +565,9 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
 // ---------------------------------------------------------------------------------------------
 // One token, tables built in the kernel.
 //
-// With a single token the tables of a whole K segment (24 tiles = 768 tables = 24 KB) fit in LDS next
-// to three or four other workgroups.  The workgroup builds them itself from the activations of its
-// segment (6 KB) while its first weight tiles are on their way, so a decode step needs no launch for
+// With a single token the tables of a whole K segment (at most 32 tiles = 1024 tables = 32 KB) fit in LDS
+// next to three or more other workgroups.  The workgroup builds them itself from the activations of its
+// segment (at most 8 KB) while its first weight tiles are on their way, so a decode step needs no launch for
 // the table precompute, no table traffic between the two kernels, and no per-tile copy of a table
 // slice into LDS.  The entries have the values build_lut_kernel computes (fp32 sums in ascending order,
 // one rounding to fp16), as have the group sums (same tree of additions).
@@ -649,9 +656,9 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
     using Cfg = GemvCfg<B, 1, GQ, HZ>;
     constexpr int D = Cfg::D;
     constexpr int TPG = GQ / kLutGroup;  // tables per quantization group: 8, 16 or 32 consecutive lanes
-    __shared__ __attribute__((aligned(1024))) uint8_t tables[kGemvXSegmentTiles * kTableBytesPerKTile];
-    __shared__ float sums[kGemvXSegmentTiles * Cfg::GPT];
-    __shared__ float red[kWaves][kRows];
+    // LDS of a workgroup: the tables of its segment, their group sums, the four partial sums of each row.  The
+    // launch sizes it for the longest segment among its GEMVs, so short segments leave room for more workgroups.
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds_x[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -679,6 +686,10 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
     src.w_bytes = (uint32_t)(n_ktiles * Cfg::TB);
     src.t_bytes = src.s_bytes = 0;
 
+    const uint32_t lt = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)lds_x));
+    const uint32_t ls = lt + (uint32_t)seg_tiles * kTableBytesPerKTile;  // group sums follow the tables
+    const uint32_t lr = ls + (uint32_t)seg_tiles * Cfg::GPT * 4;         // then the partial sums [wave][row]
+
     // first weight tiles on their way before anything else
     Stage<B, 1, Cfg::MPL> st[D] = {};
 #pragma unroll
@@ -690,14 +701,13 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
         const int n_tab = (k1 - k0) * kTablesPerKTile;
         constexpr int kPasses = kGemvXSegmentTiles * kTablesPerKTile / (kWaves * 64);
         static_assert(kPasses * kWaves * 64 == kGemvXSegmentTiles * kTablesPerKTile, "whole passes");
-        u32x2 xv[kPasses];
+        u32x2 xv[kPasses];  // all requests first (a pass beyond the segment reads activations nobody uses)
 #pragma unroll
         for (int i = 0; i < kPasses; ++i)
             xv[i] = __builtin_amdgcn_raw_buffer_load_b64(rx, (i * kWaves * 64 + tid) * 8, k0 * kKTile * 2, 0);
-        const uint32_t lt = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)tables));
-        const uint32_t ls = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<float>)sums));
 #pragma unroll
         for (int i = 0; i < kPasses; ++i) {
+            if (i * kWaves * 64 >= n_tab) break;
             const int j = i * kWaves * 64 + tid;
             // (copy the elements out first: a bit cast applied directly to a vector element reads element 0)
             const uint32_t w01 = xv[i].x, w23 = xv[i].y;
@@ -732,8 +742,6 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
     uint32_t sel[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) sel[k] = 0x03020100u | (uint32_t)(4 + k);
-    const uint32_t lt = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)tables));
-    const uint32_t ls = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<float>)sums));
     float y = 0.f;
     for (int base = t0; base < t1; base += D) {
 #pragma unroll
@@ -753,10 +761,11 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
         }
     }
 
-    red[wave][lane] = y;
+    store_lds<float>(lr + (wave * kRows + lane) * 4, y);
     __syncthreads();
     if (wave != 0) return;
-    y = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    y = ((load_lds<float>(lr + lane * 4) + load_lds<float>(lr + (kRows + lane) * 4)) +
+         load_lds<float>(lr + (2 * kRows + lane) * 4)) + load_lds<float>(lr + (3 * kRows + lane) * 4);
     float yy[1] = {y};
     finish_rows<1>(d, rb, seg, n_seg, lane, yy);
 }
@@ -817,40 +826,48 @@ int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc
     return launch_format<false>(bits, has_zero, padded_tokens(N), group, a, max_workgroups, st);
 }
 
+// LDS of a workgroup whose segment has `seg_tiles` tiles: tables, group sums (at most 4 per tile), partial sums
+static unsigned x_lds_bytes(int seg_tiles) {
+    return (unsigned)seg_tiles * (kTableBytesPerKTile + 4 * 4) + kWaves * kRows * 4;
+}
+
 template <int B, bool HZ, bool SINGLE>
-static int launch_x_group(int group, const KernelArgs<SINGLE>& a, int n_wg, hipStream_t st) {
+static int launch_x_group(int group, const KernelArgs<SINGLE>& a, int n_wg, int max_seg_tiles, hipStream_t st) {
     const dim3 grid((unsigned)n_wg, (unsigned)a.n_gemv), block(kWaves * 64);
+    const unsigned lds = x_lds_bytes(max_seg_tiles);
     switch (group) {
-        case 32: hipLaunchKernelGGL((mpgemv_x_kernel<B, 32, HZ, SINGLE>), grid, block, 0, st, a); break;
-        case 64: hipLaunchKernelGGL((mpgemv_x_kernel<B, 64, HZ, SINGLE>), grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL((mpgemv_x_kernel<B, 128, HZ, SINGLE>), grid, block, 0, st, a); break;
+        case 32: hipLaunchKernelGGL((mpgemv_x_kernel<B, 32, HZ, SINGLE>), grid, block, lds, st, a); break;
+        case 64: hipLaunchKernelGGL((mpgemv_x_kernel<B, 64, HZ, SINGLE>), grid, block, lds, st, a); break;
+        default: hipLaunchKernelGGL((mpgemv_x_kernel<B, 128, HZ, SINGLE>), grid, block, lds, st, a); break;
     }
     return launch_status();
 }
 
 template <bool SINGLE>
-static int launch_x_format(int bits, int has_zero, int group, const KernelArgs<SINGLE>& a, int n_wg, hipStream_t st) {
+static int launch_x_format(int bits, int has_zero, int group, const KernelArgs<SINGLE>& a, int n_wg, int max_seg_tiles,
+                           hipStream_t st) {
     if (bits == 1) {
-        return has_zero ? launch_x_group<1, true, SINGLE>(group, a, n_wg, st)
-                        : launch_x_group<1, false, SINGLE>(group, a, n_wg, st);
+        return has_zero ? launch_x_group<1, true, SINGLE>(group, a, n_wg, max_seg_tiles, st)
+                        : launch_x_group<1, false, SINGLE>(group, a, n_wg, max_seg_tiles, st);
     }
-    if (bits == 2) return launch_x_group<2, true, SINGLE>(group, a, n_wg, st);
-    return launch_x_group<4, true, SINGLE>(group, a, n_wg, st);
+    if (bits == 2) return launch_x_group<2, true, SINGLE>(group, a, n_wg, max_seg_tiles, st);
+    return launch_x_group<4, true, SINGLE>(group, a, n_wg, max_seg_tiles, st);
 }
 
 int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y, void* workspace, hipStream_t st) {
     KernelArgs<true> a;
     fill_desc_x(a.single, L, packed, x, y, workspace);
     a.n_gemv = 1;
-    return launch_x_format<true>(L.bits, L.has_zero, L.group, a, plan_gemv_x(L).n_workgroups, st);
+    const GemvPlan p = plan_gemv_x(L);
+    return launch_x_format<true>(L.bits, L.has_zero, L.group, a, p.n_workgroups, p.seg_tiles, st);
 }
 
 int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
-                          hipStream_t st) {
+                          int max_seg_tiles, hipStream_t st) {
     KernelArgs<false> a;
     a.descs = descs_dev;
     a.n_gemv = n_gemv;
-    return launch_x_format<false>(bits, has_zero, group, a, max_workgroups, st);
+    return launch_x_format<false>(bits, has_zero, group, a, max_workgroups, max_seg_tiles, st);
 }
 
 // copies up to 16 descriptors per launch from the kernel arguments into the device table
