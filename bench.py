@@ -34,7 +34,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 # WRITE_SIZE runs of this script scaled by a plain copy of known size (--calibration-copy); the counters
 # cannot be read from inside the process.  Source: profiles/mpgemv_7b_w2g64_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    ("mpgemv_x", "7b_w2g64", 1): 63_912_960 + 525_517,
+    ("mpgemv_x", "7b_w2g64", 1): 63_697_920 + 160_768,
     ("mpgemm", "prefill_w4g64", 1024): 92_630_221 + 22_544_384,
 }
 
