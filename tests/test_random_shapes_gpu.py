@@ -27,3 +27,32 @@ def test_random_shapes(oracle_lib, block):
         y = (mpgemv, mpgemv_x, mpgemm)[kind](shape, pack(shape, q, s, z), x)
         err = oracle.row_relative_error(y, oracle.matmul(q, s, z, x, bits, group)).max()
         assert np.isfinite(err) and err <= TOL, f"{('mpgemv', 'mpgemv_x', 'mpgemm')[kind]} {shape} N={N}: {err:.3e}"
+
+
+def test_ternary_weights_with_one_scale_per_tensor(oracle_lib):
+    """The paper's BitNet configuration (Sec. 6.1: ternary weights treated as 2-bit, one scale per tensor; kernel
+    shapes 2560 / 6912) expressed in the group format: codes in {0, 1, 2}, zero = 1, every group the same scale.
+    Decode (both forms) and prefill against the oracle; with scale 1 and small integer activations the
+    result is an exact integer."""
+    import synth
+    M, K, bits, group = 2560, 6912, 2, 64
+    q = (synth.uniform_codes(901, M * K, 2) % 3).astype(np.uint8).reshape(M, K)
+    z = np.ones((M, K // group), dtype=np.float16)
+    s = np.full((M, K // group), 0.0123, dtype=np.float16)
+    shape = tman.Shape(M, K, bits, group)
+    blob = pack(shape, q, s, z)
+    x = synth.normal_fp16(902, 3 * K).reshape(3, K)
+    Y = oracle.matmul(q, s, z, x, bits, group)
+    assert oracle.row_relative_error(mpgemv(shape, blob, x), Y).max() <= TOL
+    assert oracle.row_relative_error(mpgemv_x(shape, blob, x[:1]), Y[:1]).max() <= TOL
+    assert oracle.row_relative_error(mpgemm(shape, blob, x), Y).max() <= TOL
+    # exact case: scale 1, activations in {-1, 0, 1}: every partial sum is a small integer
+    ones = np.ones_like(s)
+    xi = (synth.uniform_codes(903, K, 2) % 3).astype(np.int64).reshape(1, K) - 1
+    ref = xi @ (q.astype(np.int64) - 1).T
+    assert np.abs(ref).max() < 2048
+    blob1 = pack(shape, q, ones, z)
+    xf = xi.astype(np.float16)
+    assert np.array_equal(mpgemv_x(shape, blob1, xf).astype(np.int64), ref)
+    assert np.array_equal(mpgemv(shape, blob1, xf).astype(np.int64), ref)
+    assert np.array_equal(mpgemm(shape, blob1, xf).astype(np.int64), ref)
