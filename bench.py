@@ -32,7 +32,7 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per launch of the dominant kernels on the default workloads, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script scaled by a plain copy of known size (--calibration-copy); the counters
-# cannot be read from inside the process.  Source: profiles/mpgemv_7b_w2g64_hbm_traffic.txt.
+# cannot be read from inside the process.  Source: profiles/mpgemv_x_7b_w2g64_and_mpgemm_w4g64_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
     ("mpgemv_x", "7b_w2g64", 1): 63_697_920 + 160_768,
     ("mpgemm", "prefill_w4g64", 1024): 92_630_221 + 22_544_384,
