@@ -24,6 +24,11 @@
 //     coherent across the chip without cache write-back or invalidation.
 // All GEMVs of a decode step can share one launch (descriptor table), so the machine is filled even
 // though one layer alone is too small.
+//
+// Two kernels follow.  mpgemv_kernel serves 1 to 8 tokens and reads the tables tman_build_lut made
+// (Sec. 5: the precompute as a kernel of its own, shared by the layers fed from one activation).
+// mpgemv_x_kernel serves one token and builds the tables of its K segment itself, in LDS, from the
+// activations: the same lookups, but a decode step is a single launch and no table ever reaches memory.
 #include <hip/hip_fp16.h>
 
 #include <type_traits>
