@@ -63,11 +63,7 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? TMAN_OK : 
 
 // Decode scheduling: a workgroup (four waves) owns one row block and one K segment of at most this
 // many tiles; longer K is cut into equal segments that meet through the workspace.
-#ifdef TMAN_SEG
-constexpr int kGemvSegmentTiles = TMAN_SEG;
-#else
 constexpr int kGemvSegmentTiles = 32;
-#endif
 constexpr int kGemvManyTokensSegmentTiles = 24;  // for 4 or 8 tokens
 
 // One GEMV of a decode launch, as the kernel sees it.

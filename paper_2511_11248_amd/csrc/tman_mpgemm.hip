@@ -21,6 +21,8 @@
 // (fp32 accumulation) from the ring; one barrier per 32-column stage.
 #include <hip/hip_fp16.h>
 
+#include <mutex>
+
 #include "tman_internal.h"
 
 namespace tman {
@@ -445,7 +447,8 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
                 }
             }
         }
-        // loads of stages past the end may still be on their way to LDS, which the epilogue reuses
+        // Loads of stages past the end (zero-sized sources: they write zeros) may still be on their way to
+        // LDS, which the epilogue reuses: they must have landed before any wave passes the barrier below.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     } else {
         // ---------------------------------------------------------------- consumer
@@ -500,6 +503,9 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
 
     // epilogue: accumulators -> fp16 -> LDS as [token][row] -> coalesced 16-byte stores
     // C[i][j] of a 32x32 block: i = row (8 * (v / 4) + 4 * h + v % 4), j = token (lane % 32)
+    // One more barrier between the last stage and the epilogue: the consumers leave the last stage barrier
+    // while activation loads of the padding stages, issued by the producers, can still be writing to the ring.
+    __syncthreads();
     uint8_t* otile = smem;  // the stage buffers are free now
     if (wave < kConsumerWaves) {
 #pragma unroll
@@ -540,13 +546,14 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
 
 template <int B, int GQ, bool HZ, int RB>
 static int launch_tile(GemmArgs a, hipStream_t st) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&mpgemm_kernel<B, GQ, HZ, RB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, Tile<RB>::LdsBytes) != hipSuccess)
-            return TMAN_ERR_LAUNCH;
-        attr_set = true;
-    }
+    // once per kernel instantiation, also when several host threads make their first call together
+    static std::once_flag once;
+    static hipError_t attr_rc = hipSuccess;
+    std::call_once(once, [] {
+        attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&mpgemm_kernel<B, GQ, HZ, RB>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, Tile<RB>::LdsBytes);
+    });
+    if (attr_rc != hipSuccess) return TMAN_ERR_LAUNCH;
     a.m_tiles = (a.n_row_blocks + RB - 1) / RB;
     a.n_tiles = (a.N + kTN - 1) / kTN;
     const unsigned grid = (unsigned)((a.m_tiles + kXcds - 1) / kXcds * kXcds * a.n_tiles);
@@ -558,14 +565,14 @@ static int launch_tile(GemmArgs a, hipStream_t st) {
 // compute units times rows per workgroup, with a small bonus for larger tiles (fewer operand reads
 // and less dequantization per MFMA).
 static int choose_row_blocks(int n_row_blocks, int N) {
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            n_cu = prop.multiProcessorCount;
-        if (n_cu <= 0) n_cu = 256;
-    }
+    static std::once_flag once;
+    static int n_cu = 256;  // assumed when no device answers
+    std::call_once(once, [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            n_cu = n;
+    });
     const int n_tiles = (N + kTN - 1) / kTN;
     // A grid that leaves compute units idle even with one row block per workgroup: the time of a workgroup
     // is then set by the chain load -> dequantize -> barrier of its stages, shortest with the smallest tile.

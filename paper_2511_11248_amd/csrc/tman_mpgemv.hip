@@ -700,16 +700,19 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
 #pragma unroll
     for (int s = 0; s < D; ++s) issue_weights<B, 1, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
 
-    // tables and group sums of the segment: thread -> tables tid, tid + 256, ... (x beyond K reads as zero)
+    // tables and group sums of the segment: thread -> tables tid, tid + 256, ... (x beyond K reads as zero).
+    // The range check of a buffer load covers the per-lane offset only, not the scalar offset, so the resource
+    // starts at the segment's first activation and ends with x: K * 2 bytes less the segment's start.
     {
-        const rsrc_t rx = make_rsrc(uniform(d.lut_t), (uint32_t)uniform(d.K) * 2u);
+        const uint32_t x_start = (uint32_t)(k0 * kKTile * 2);  // k0 < n_ktiles, so this lies inside x
+        const rsrc_t rx = make_rsrc(uniform(d.lut_t) + x_start, (uint32_t)uniform(d.K) * 2u - x_start);
         const int n_tab = (k1 - k0) * kTablesPerKTile;
         constexpr int kPasses = kGemvXSegmentTiles * kTablesPerKTile / (kWaves * 64);
         static_assert(kPasses * kWaves * 64 == kGemvXSegmentTiles * kTablesPerKTile, "whole passes");
         u32x2 xv[kPasses];  // all requests first (a pass beyond the segment reads activations nobody uses)
 #pragma unroll
         for (int i = 0; i < kPasses; ++i)
-            xv[i] = __builtin_amdgcn_raw_buffer_load_b64(rx, (i * kWaves * 64 + tid) * 8, k0 * kKTile * 2, 0);
+            xv[i] = __builtin_amdgcn_raw_buffer_load_b64(rx, (i * kWaves * 64 + tid) * 8, 0, 0);
 #pragma unroll
         for (int i = 0; i < kPasses; ++i) {
             if (i * kWaves * 64 >= n_tab) break;

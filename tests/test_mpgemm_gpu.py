@@ -99,3 +99,47 @@ def test_every_tile_height(oracle_lib, M, rows):
     Y = oracle.matmul(q, s, z, x[tokens], bits, group)
     err = oracle.row_relative_error(y[tokens], Y)
     assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
+
+
+@pytest.mark.parametrize("poison", [float("nan"), float("inf")])
+@pytest.mark.parametrize("M,K,bits,group,N", [(70, 160, 4, 32, 300), (200, 1056, 2, 32, 513), (64, 96, 1, 32, 7)])
+def test_activations_and_outputs_stay_inside_their_buffers(oracle_lib, poison, M, K, bits, group, N):
+    """X and Y are slices of tensors filled with NaN / Inf; the last token tile is ragged (N % 256 != 0) and K
+    is not a multiple of the 128-column tile.  A read beyond X would reach the result as NaN, a write beyond Y
+    would overwrite the filler."""
+    import torch
+    from gpu_helpers import dev
+
+    hz = bits != 1
+    q, s, z, x = rand_case(4000 + M + K + N, M, K, N, bits, group, hz)
+    shape = tman.Shape(M, K, bits, group, hz)
+    blob = pack(shape, q, s, z)
+    xbig = torch.full((512 + N * K + 70000,), poison, dtype=torch.float16, device=dev())
+    xbig[512:512 + N * K] = to_dev(x).reshape(-1)
+    xs = xbig[512:512 + N * K].view(N, K)
+    ybig = torch.full((64 + N * M + 64,), poison, dtype=torch.float16, device=dev())
+    ys = ybig[64:64 + N * M].view(N, M)
+    tman.tman_mpgemm(shape, blob, xs, N, ys, None)
+    torch.cuda.synchronize()
+    y = ys.cpu().numpy()
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    assert oracle.row_relative_error(y, oracle.matmul(q, s, z, x, bits, group)).max() <= TOL
+    filler = torch.cat([ybig[:64], ybig[64 + N * M:]])
+    assert bool(torch.isnan(filler).all() if poison != poison else torch.isinf(filler).all())
+
+
+@pytest.mark.parametrize("M,rows", [(16384, 64), (32768, 128), (49152, 192), (65536, 256)])
+def test_every_token_of_a_full_tile_at_every_tile_height(oracle_lib, M, rows):
+    """All 256 tokens of one full token tile, for each tile height, against the oracle on the first two and the
+    last workgroup's rows (every token row of the output tile that is staged through LDS in the epilogue,
+    including the part of it that overlaps the stage ring's activation slots)."""
+    K, bits, group, N = 256, 4, 64, 256
+    shape = tman.Shape(M, K, bits, group, True)
+    assert tman.tman_mpgemm_tile_rows(shape, N) == rows
+    q, s, z, x = rand_case(6000 + M, M, K, N, bits, group)
+    y = mpgemm(shape, pack(shape, q, s, z), x)
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    sel = np.r_[0:2 * rows, M - rows:M]
+    Y = oracle.matmul(q[sel], s[sel], z[sel], x, bits, group)
+    err = oracle.row_relative_error(y[:, sel], Y)
+    assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"

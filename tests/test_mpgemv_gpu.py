@@ -230,3 +230,28 @@ def test_largest_batch(oracle_lib):
     torch.cuda.synchronize()
     for y, (q, s, z, x) in zip(ys, refs):
         assert oracle.row_relative_error(y.cpu().numpy(), oracle.matmul(q, s, z, x, bits, group)).max() <= TOL
+
+
+@pytest.mark.parametrize("poison", [float("nan"), float("inf")])
+@pytest.mark.parametrize("M,K,bits,group,N", [(70, 160, 4, 32, 3), (130, 4672, 4, 64, 1), (64, 4000, 2, 32, 8)])
+def test_activations_and_outputs_stay_inside_their_buffers(oracle_lib, poison, M, K, bits, group, N):
+    """x (read by tman_build_lut) and y (written by tman_mpgemv) are slices of tensors filled with NaN / Inf.
+    A read beyond x reaches the result (the padded groups have zero scale and zero, which hides finite
+    values but not 0 * NaN); a write beyond y overwrites the filler.  Ragged K, tokens padded to 4 / 8."""
+    q, s, z, x = rand_case(88 + K, M, K, N, bits, group)
+    shape = tman.Shape(M, K, bits, group)
+    blob = pack(shape, q, s, z)
+    xbig = torch.full((1024 + N * K + 8192,), poison, dtype=torch.float16, device=dev())
+    xbig[1024:1024 + N * K] = to_dev(x).reshape(-1)
+    xs = xbig[1024:1024 + N * K].view(N, K)
+    ybig = torch.full((64 + N * M + 64,), poison, dtype=torch.float16, device=dev())
+    ys = ybig[64:64 + N * M].view(N, M)
+    lut = torch.empty(tman.tman_lut_bytes(N, K, group), dtype=torch.uint8, device=dev())
+    tman.tman_build_lut(xs, N, K, group, lut)
+    tman.tman_mpgemv(shape, blob, lut, N, ys, gemv_workspace(shape, N))
+    torch.cuda.synchronize()
+    y = ys.cpu().numpy()
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    assert oracle.row_relative_error(y, oracle.matmul(q, s, z, x, bits, group)).max() <= TOL
+    filler = torch.cat([ybig[:64], ybig[64 + N * M:]])
+    assert bool(torch.isnan(filler).all() if poison != poison else torch.isinf(filler).all())

@@ -88,17 +88,46 @@ def test_deterministic_and_workspace_reusable(oracle_lib):
     assert oracle.row_relative_error(y1, oracle.matmul(q, s, z, x, bits, group)).max() <= TOL
 
 
-def test_activation_buffer_is_read_within_bounds(oracle_lib):
-    """K = 160: the second tile's tables past column 160 must read as zero, not as whatever follows x."""
-    M, K, bits, group = 64, 160, 4, 32
-    q, s, z, x = rand_case(77, M, K, 1, bits, group)
+def _embedded(values, poison, lead=1024, tail=8192):
+    """A device tensor filled with `poison` that holds `values` (fp16, 1-D) at element `lead` (16-byte aligned);
+    returns (whole tensor, the slice holding the values)."""
+    big = torch.full((lead + values.numel() + tail,), poison, dtype=torch.float16, device=dev())
+    big[lead:lead + values.numel()] = values
+    return big, big[lead:lead + values.numel()]
+
+
+@pytest.mark.parametrize("poison", [float("nan"), float("inf")])
+@pytest.mark.parametrize("M,K,bits,group", [
+    (64, 160, 4, 32),     # one segment; the second tile's tables past column 160 must read as zero
+    (130, 4672, 4, 64),   # 37 tiles -> two segments of 19; the last tile of the LAST segment is half beyond K
+    (70, 11040, 2, 32),   # 87 tiles -> four segments of 22; the last has 21 tiles, the last tile a quarter used
+])
+def test_activations_and_outputs_stay_inside_their_buffers(oracle_lib, poison, M, K, bits, group):
+    """x and y are slices of larger tensors filled with NaN (Inf): whatever the kernel reads beyond x would
+    reach the result (0 * NaN is NaN: the padded groups have zero scale and zero, which hides any finite
+    value), and whatever it writes beyond y would overwrite the filler.  Single call and batch form."""
+    q, s, z, x = rand_case(77 + K, M, K, 1, bits, group)
     shape = tman.Shape(M, K, bits, group)
-    big = torch.full((4096,), 1000.0, dtype=torch.float16, device=dev())  # x sits inside a buffer of large values
-    big[1024:1024 + K] = to_dev(x)[0]
-    y = torch.empty((1, M), dtype=torch.float16, device=dev())
-    tman.tman_mpgemv_x(shape, pack(shape, q, s, z), big[1024:1024 + K], y, gemv_workspace(shape, 1))
+    blob = pack(shape, q, s, z)
+    Y = oracle.matmul(q, s, z, x, bits, group)
+    xbig, xs = _embedded(to_dev(x)[0], poison)
+    ybig, ys = _embedded(torch.zeros(M, dtype=torch.float16, device=dev()), poison, lead=64, tail=64)
+    tman.tman_mpgemv_x(shape, blob, xs, ys, gemv_workspace(shape, 1))
     torch.cuda.synchronize()
-    assert oracle.row_relative_error(y.cpu().numpy(), oracle.matmul(q, s, z, x, bits, group)).max() <= TOL
+    y = ys.cpu().numpy().reshape(1, M)
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    assert oracle.row_relative_error(y, Y).max() <= TOL
+    filler = torch.cat([ybig[:64], ybig[64 + M:]])
+    assert bool(torch.isnan(filler).all() if poison != poison else torch.isinf(filler).all())
+    # batch form: the same GEMV twice in one launch, sharing the activation slice
+    y2 = [torch.zeros((1, M), dtype=torch.float16, device=dev()) for _ in range(2)]
+    wss = [gemv_workspace(shape, 1) for _ in range(2)]
+    desc = torch.empty(tman.tman_mpgemv_batch_desc_bytes(2), dtype=torch.uint8, device=dev())
+    tman.tman_mpgemv_x_batch_prepare([shape, shape], [blob, blob], [xs, xs], y2, wss, desc)
+    tman.tman_mpgemv_x_batch_run([shape, shape], desc)
+    torch.cuda.synchronize()
+    for yy in y2:
+        assert np.array_equal(yy.cpu().numpy().view(np.uint16), y.view(np.uint16))
 
 
 @pytest.mark.parametrize("name", ["7b_w2g64", "7b_w4g128", "3p8b_w2g64", "3p8b_w1g64"])
