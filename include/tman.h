@@ -185,6 +185,28 @@ int tman_mpgemm(const tman_shape_t *shape, const void *packed, const void *x, in
  */
 int32_t tman_mpgemm_tile_rows(const tman_shape_t *shape, int32_t N);
 
+/*
+ * tman_mpgemv for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as tman_mpgemv, but the
+ * workspace (tickets and partial sums of the K segments) is a fixed array of TMAN_NOALLOC_SCRATCH_BYTES in
+ * device memory that the library owns (each GPU the library runs on holds it until the process ends).  The
+ * call allocates and frees nothing.
+ *   - shapes / N whose tman_mpgemv_workspace_bytes exceeds TMAN_NOALLOC_SCRATCH_BYTES are refused with
+ *     TMAN_ERR_WORKSPACE (nothing is launched);
+ *   - every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU (different
+ *     streams, or several host threads) race and must be serialised by the caller, or use tman_mpgemv
+ *     with workspaces of their own;
+ *   - the array keeps what the last call left: the tickets are back at zero after every call, the partial
+ *     sums are overwritten before they are read, so nothing is cleared between calls.
+ * tman_noalloc_init resolves the array's device address on the CURRENT device (the first
+ * tman_mpgemv_noalloc call on a device does the same); call it once per device at set-up, outside any graph
+ * capture.  Both return TMAN_ERR_LAUNCH when the HIP runtime cannot provide the address.
+ */
+#define TMAN_NOALLOC_SCRATCH_BYTES (2 * 1024 * 1024)
+int tman_noalloc_init(void);
+int tman_mpgemv_noalloc(const tman_shape_t *shape, const void *packed, const void *lut, int32_t N, void *y,
+                        void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *tman_status_string(int status);
 

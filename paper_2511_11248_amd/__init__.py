@@ -17,6 +17,8 @@ from .api import (  # noqa: F401
     tman_build_lut_batch,
     tman_mpgemv,
     tman_mpgemm,
+    tman_noalloc_init,
+    tman_mpgemv_noalloc,
     tman_mpgemm_tile_rows,
     tman_mpgemv_batch_desc_bytes,
     tman_mpgemv_batch_prepare,

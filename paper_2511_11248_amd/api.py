@@ -90,6 +90,10 @@ def _load():
         L.tman_mpgemm.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
         L.tman_mpgemm_tile_rows.restype = C.c_int32
         L.tman_mpgemm_tile_rows.argtypes = [sp, C.c_int32]
+        L.tman_noalloc_init.restype = C.c_int
+        L.tman_noalloc_init.argtypes = []
+        L.tman_mpgemv_noalloc.restype = C.c_int
+        L.tman_mpgemv_noalloc.argtypes = [sp, vp, vp, C.c_int32, vp, vp]
         L.tman_status_string.restype = C.c_char_p
         L.tman_status_string.argtypes = [C.c_int]
         L.tman_layout_version.restype = C.c_int32
@@ -174,6 +178,16 @@ def tman_mpgemv(shape: Shape, packed, lut, N: int, y, workspace, stream=None) ->
     wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
     _check(_load().tman_mpgemv(C.byref(shape.c()), _ptr(packed), _ptr(lut), N, _ptr(y), _ptr(workspace), wb,
                                _stream(stream)), "tman_mpgemv")
+
+
+def tman_noalloc_init() -> None:
+    _check(_load().tman_noalloc_init(), "tman_noalloc_init")
+
+
+def tman_mpgemv_noalloc(shape: Shape, packed, lut, N: int, y, stream=None) -> None:
+    """tman_mpgemv with the library's own fixed scratch array as workspace (allocates nothing)."""
+    _check(_load().tman_mpgemv_noalloc(C.byref(shape.c()), _ptr(packed), _ptr(lut), N, _ptr(y), _stream(stream)),
+           "tman_mpgemv_noalloc")
 
 
 def tman_mpgemm(shape: Shape, packed, x, N: int, y, workspace=None, stream=None) -> None:

@@ -236,3 +236,17 @@ def test_prefill_tile_rows_query(lib):
     assert tman.tman_mpgemm_tile_rows(tman.Shape(65536, 384, 4, 64, True), 200) == 256
     assert tman.tman_mpgemm_tile_rows(tman.Shape(256, 500, 4, 64, True), 128) == 0
     assert tman.tman_mpgemm_tile_rows(tman.Shape(256, 512, 4, 64, True), 0) == 0
+
+
+def test_noalloc_entry_point_validates_before_touching_the_gpu(lib):
+    ok = _shape(M=64, K=256)
+    assert lib.tman_mpgemv_noalloc(None, FAKE, FAKE, 1, FAKE, None) == -1
+    assert lib.tman_mpgemv_noalloc(C.byref(ok), None, FAKE, 1, FAKE, None) == -1
+    assert lib.tman_mpgemv_noalloc(C.byref(ok), FAKE, FAKE, 0, FAKE, None) == -4
+    assert lib.tman_mpgemv_noalloc(C.byref(ok), FAKE, FAKE, 9, FAKE, None) == -4
+    assert lib.tman_mpgemv_noalloc(C.byref(ok), FAKE + 8, FAKE, 1, FAKE, None) == -6
+    assert lib.tman_mpgemv_noalloc(C.byref(_shape(bits=3)), FAKE, FAKE, 1, FAKE, None) == -2
+    # the fixed array is 2 MiB: a workspace beyond it is refused on the sizes alone
+    huge = _shape(M=1 << 20, K=16384)
+    assert tman.tman_mpgemv_workspace_bytes(tman.Shape(1 << 20, 16384, 4, 64), 8) > 2 * 1024 * 1024
+    assert lib.tman_mpgemv_noalloc(C.byref(huge), FAKE, FAKE, 8, FAKE, None) == -5
