@@ -2,17 +2,18 @@
 """Benchmark of the T-MAN hot path on one MI355X.
 
 Headline (the benchmark spec metric, configs[1]): decode mpGEMV weight GB/s on the 7B-style layer set,
-uint2 weights, group 64, N = 1.  One step = one pass over the layer set, activations in, outputs out:
-the lookup-table precompute and the five table-lookup GEMVs (qkv, o, gate, up, down), in one launch
-whose workgroups build the tables of their own K segment (the two-launch form, a table kernel followed
-by a lookup kernel, is timed beside it).
-To keep the 256 MB Infinity Cache from serving the weights, the steps rotate over 32 independent
-copies of the layer set (2 GB of packed weights); all inputs are resident in HBM before timing.
+uint2 weights, group 64, N = 1.  One step = one token through a 32-layer decoder built from that layer
+set: 32 launches, one per layer, each layer with packed weights of its own (2 GB in all, so the 256 MB
+Infinity Cache cannot serve them).  A launch takes the layer's activations in and gives its outputs: the
+lookup-table precompute and the five table-lookup GEMVs (qkv, o, gate, up, down) run in one kernel whose
+workgroups build the tables of their own K segment (the two-launch form, a table kernel followed by a
+lookup kernel, is timed beside it).  All inputs are resident in HBM before timing.
 
-The same JSON line also carries the prefill mpGEMM figure (11008 x 4096 uint4 g64, N = 1024) as a
-secondary object, the roofline fraction of the dominant kernel (its average launch duration from HIP
-events that cut the timed region into runs of launches) and the fp64 CPU oracle timed on the host cores
-over a bounded sample.
+The same JSON line carries: the error of the timed configuration against the fp64 CPU oracle; the prefill
+mpGEMM figure (11008 x 4096 uint4 g64, N = 1024) with its error; `configs`, every other BASELINE
+configuration timed briefly the same way with its error; the roofline fraction of the dominant kernel
+(its average launch duration from HIP events that cut the timed region into runs of launches); and the
+oracle timed on the host cores over a bounded sample.
 """
 from __future__ import annotations
 
@@ -42,8 +43,8 @@ MEASURED_TRAFFIC_BYTES = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="7b_w2g64")
     ap.add_argument("--instances", type=int, default=0, help="copies of the layer set to rotate over (0 = workload default)")
     ap.add_argument("--prefill-tokens", type=int, default=1024)
@@ -59,8 +60,14 @@ def parse():
                     help="skip the context figures (cache-resident, two-launch, device copy): under a profiler the "
                          "kernel statistics then cover the timed, cache-cold launches only")
     ap.add_argument("--table", action="store_true",
-                    help="instead of the headline line: time every configuration (decode workloads at their token "
-                         "counts, prefill at 256/1024/2048 tokens), check each against the CPU oracle, and print a table")
+                    help="after the JSON line, print the same figures (headline, prefill, every other configuration) "
+                         "as a table on stderr")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the `configs` array (every other BASELINE configuration, timed briefly and checked "
+                         "against the oracle): under a profiler the statistics then cover the headline workloads only")
+    ap.add_argument("--preroll", type=int, default=300,
+                    help="untimed launches before the declared warm-up: clocks and caches reach their steady state, so "
+                         "a short timed region reads what a long one reads")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device-to-device copy of 256 MiB before the timed region: under "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE its known traffic calibrates the counters")
@@ -122,107 +129,100 @@ def decode_job(torch, tman, synth, dev, w, N, n_inst):
             "keep": (blobs, xs, luts, wss, descs, x_descs)}  # the launches hold raw pointers into these
 
 
-def whole_model_row(torch, tman, synth, oracle, dev, w, job, emit):
+def timed_steps(torch, step, warm, steps):
+    """Wall clock per step over `steps` calls of step(i) after `warm` untimed ones (device idle on both sides)."""
+    for i in range(warm):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def decode_step_fn(job, n_inst):
+    stream = job["stream"]
+    if job["x_calls"] is not None:  # one token: one launch
+        return lambda i: job["x_calls"][i % n_inst](stream)
+
+    def two(i):
+        job["lut_calls"][i % n_inst](stream)
+        job["gemv_calls"][i % n_inst](stream)
+
+    return two
+
+
+def decode_error(torch, synth, oracle, w, job, N, inst=0):
+    """Largest row-normalised error of the outputs of the step on copy `inst` against the fp64 oracle, and the
+    oracle's time."""
+    decode_step_fn(job, max(inst + 1, 1))(inst)
+    torch.cuda.synchronize()
+    err, cpu_t, used = 0.0, 0.0, 1
+    for li in range(len(job["shapes"])):
+        q, sc, z = synth.layer_tensors(w, inst, li)
+        xh = synth.activation(w, inst, li, N)
+        c0 = time.perf_counter()
+        Y, used = oracle.matmul(q, sc, z, xh, w.bits, w.group, return_threads=True)
+        cpu_t += time.perf_counter() - c0
+        err = max(err, float(oracle.row_relative_error(job["ys"][li].cpu().numpy().astype(np.float64), Y).max()))
+    return err, cpu_t, used
+
+
+def whole_model_launch(torch, tman, dev, w, job):
     """BASELINE config 4 asks for the weight stream of a whole 32-layer decoder in one decode step, every GEMV
-    with an activation of its own (nothing runs between the layers): all 32 x 5 GEMVs go into ONE launch."""
+    with an activation of its own (nothing runs between the layers): all 32 x 5 GEMVs in ONE launch."""
     blobs, xs = job["keep"][0], job["keep"][1]
-    layers = w.layers
-    acts = []
-    for l in layers:
-        if l.act not in acts:
-            acts.append(l.act)
+    acts = job["acts"]
     shapes, pk, xx, ys, wss = [], [], [], [], []
     for inst in range(w.instances):
-        for li, l in enumerate(layers):
+        for li, l in enumerate(w.layers):
             sh = job["shapes"][li]
             shapes.append(sh); pk.append(blobs[inst][li]); xx.append(xs[inst][acts.index(l.act)])
             ys.append(torch.empty((1, sh.M), dtype=torch.float16, device=dev))
             wss.append(torch.zeros(tman.tman_mpgemv_workspace_bytes(sh, 1), dtype=torch.uint8, device=dev))
     desc = torch.empty(tman.tman_mpgemv_batch_desc_bytes(len(shapes)), dtype=torch.uint8, device=dev)
     tman.tman_mpgemv_x_batch_prepare(shapes, pk, xx, ys, wss, desc)
-    call, stream = tman.bound_mpgemv_x_batch_run(shapes, desc), job["stream"]
-    for _ in range(5):
-        call(stream)
-    torch.cuda.synchronize()
-    reps = 50
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        call(stream)
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / reps
-    err, cpu_t, used, checked = 0.0, 0.0, 1, 0
-    for inst in (0, w.instances - 1):  # first and last layer against the oracle; its time is scaled to all layers
-        for li in range(len(layers)):
-            q, sc, z = synth.layer_tensors(w, inst, li)
-            xh = synth.activation(w, inst, li, 1)
-            c0 = time.perf_counter()
-            Y, used = oracle.matmul(q, sc, z, xh, w.bits, w.group, return_threads=True)
-            cpu_t += time.perf_counter() - c0
-            checked += 1
-            y = ys[inst * len(layers) + li].cpu().numpy().astype(np.float64)
-            err = max(err, float(oracle.row_relative_error(y, Y).max()))
-    cpu_t *= len(shapes) / checked
-    total = job["weight_bytes_per_step"] * w.instances
-    gbs = total / sec / 1e9
-    emit([f"{w.name} N=1, all {w.instances} layers = {len(shapes)} GEMVs in one launch ({total / 1e6:.0f} MB)",
-          f"{sec * 1e6:.1f}", f"{gbs:.0f} GB/s", f"{gbs / HBM_PEAK_GBS:.1%}", f"{err:.2e} (layers 0 and {w.instances - 1})",
-          f"{cpu_t * 1e3:.0f} (scaled from {checked} GEMVs)", used, f"{cpu_t / sec:.0f}x"])
+    call = tman.bound_mpgemv_x_batch_run(shapes, desc)
+    return {"call": call, "ys": ys, "n_gemv": len(shapes), "keep": (wss, desc, pk, xx)}
 
 
-def run_table(args, torch, tman, synth, dev):
-    """One row per configuration: GPU time, rate, fraction of the vendor peak, error against the fp64 CPU oracle
-    (row-normalised maximum), the oracle's own time on the host cores, and the ratio.  Decode rows rotate over
-    the workload's copies of the layer set (cold cache) and check copy 0; prefill rows check every 8th row."""
-    import oracle
+def other_configs(args, torch, tman, synth, oracle, dev):
+    """Every BASELINE configuration besides the two headline workloads, timed briefly with the headline protocol
+    (rotating copies for decode, back-to-back calls for prefill) and checked against the oracle in the same run."""
+    out = []
 
-    oracle.build()
-    rows = []
+    def add(workload, sec, rate, unit, peak, err, checked):
+        out.append({"workload": workload, "us": round(sec * 1e6, 2), "rate": round(rate, 1), "unit": unit,
+                    "frac": round(rate / peak, 4), "max_err": float(f"{err:.3e}"), "checked": checked})
 
-    def emit(r):
-        rows.append(r)
-        print("| " + " | ".join(str(c) for c in r) + " |", flush=True)
-
-    emit(["config", "GPU time (us)", "rate", "of vendor peak", "max err", "oracle time (ms)", "cores", "oracle/GPU"])
-    emit(["---"] * 8)
-    for name in ("tiny_w4g64", "7b_w2g64", "7b_w4g128", "3p8b_w2g64", "3p8b_w1g64"):
+    for name in ("tiny_w4g64", "7b_w4g128", "3p8b_w2g64", "3p8b_w1g64"):
         w = synth.WORKLOADS[name]
         for N in w.tokens:
             job = decode_job(torch, tman, synth, dev, w, N, w.instances)
-            n_inst, stream = w.instances, job["stream"]
-
-            def step(i):
-                if job["x_calls"] is not None:  # one token: one launch
-                    job["x_calls"][i % n_inst](stream)
-                else:
-                    job["lut_calls"][i % n_inst](stream)
-                    job["gemv_calls"][i % n_inst](stream)
-
-            for i in range(args.warmup):
-                step(i)
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(args.steps):
-                step(i)
-            torch.cuda.synchronize()
-            sec = (time.perf_counter() - t0) / args.steps
-            # copy 0 against the oracle
-            step(0)
-            torch.cuda.synchronize()
-            err, cpu_t, used = 0.0, 0.0, 1
-            for li, s in enumerate(job["shapes"]):
-                q, sc, z = synth.layer_tensors(w, 0, li)
-                xh = synth.activation(w, 0, li, N)
-                c0 = time.perf_counter()
-                Y, used = oracle.matmul(q, sc, z, xh, w.bits, w.group, return_threads=True)
-                cpu_t += time.perf_counter() - c0
-                err = max(err, float(oracle.row_relative_error(job["ys"][li].cpu().numpy().astype(np.float64), Y).max()))
+            step = decode_step_fn(job, w.instances)
+            sec = timed_steps(torch, step, 100, 300)
+            err, _, _ = decode_error(torch, synth, oracle, w, job, N)
             gbs = job["weight_bytes_per_step"] / sec / 1e9
-            emit([f"{name} N={N} ({n_inst} copies, {'one launch' if job['x_calls'] is not None else 'two launches'})", f"{sec * 1e6:.2f}", f"{gbs:.0f} GB/s",
-                  f"{gbs / HBM_PEAK_GBS:.1%}" if w.instances > 1 else "cache-resident", f"{err:.2e}",
-                  f"{cpu_t * 1e3:.0f}", used, f"{cpu_t / sec:.0f}x"])
-            if w.config == 4:
-                whole_model_row(torch, tman, synth, oracle, dev, w, job, emit)
-            del job
+            kind = "one launch per layer set" if job["x_calls"] is not None else "table launch + lookup launch per layer set"
+            add(f"{name} N={N}, {w.instances} rotating copies, {kind}" + (" (cache-resident: correctness only)" if w.instances == 1 else ""),
+                sec, gbs, "GB/s", HBM_PEAK_GBS, err, "all outputs of copy 0")
+            if w.config == 4:  # the whole 32-layer weight stream as one launch of 160 GEMVs
+                big = whole_model_launch(torch, tman, dev, w, job)
+                stream = job["stream"]
+                sec = timed_steps(torch, lambda i: big["call"](stream), 5, 40)
+                err = 0.0
+                for inst in (0, w.instances - 1):
+                    for li in range(len(w.layers)):
+                        q, sc, z = synth.layer_tensors(w, inst, li)
+                        Y = oracle.matmul(q, sc, z, synth.activation(w, inst, li, 1), w.bits, w.group)
+                        y = big["ys"][inst * len(w.layers) + li].cpu().numpy().astype(np.float64)
+                        err = max(err, float(oracle.row_relative_error(y, Y).max()))
+                total = job["weight_bytes_per_step"] * w.instances
+                add(f"{name} N=1, all {w.instances} layers = {big['n_gemv']} GEMVs in one launch ({total / 1e6:.0f} MB)",
+                    sec, total / sec / 1e9, "GB/s", HBM_PEAK_GBS, err, "all outputs of layers 0 and 31")
+                del big
+            del job, step
     pw = synth.WORKLOADS["prefill_w4g64"]
     spec = pw.layers[0]
     ps = tman.Shape(spec.M, spec.K, pw.bits, pw.group, True)
@@ -230,50 +230,62 @@ def run_table(args, torch, tman, synth, dev):
     pblob = torch.empty(tman.tman_packed_bytes(ps), dtype=torch.uint8, device=dev)
     tman.tman_pack_weights(ps, torch.from_numpy(q).to(dev), torch.from_numpy(sc).to(dev), torch.from_numpy(z).to(dev), pblob)
     for NP in pw.tokens:
+        if NP == args.prefill_tokens:
+            continue  # the headline prefill figure
         xh = synth.activation(pw, 0, 0, NP)
         px = torch.from_numpy(xh).to(dev)
         py = torch.empty((NP, spec.M), dtype=torch.float16, device=dev)
-        for _ in range(40):  # the clocks need a few milliseconds of this load to settle
-            tman.tman_mpgemm(ps, pblob, px, NP, py, None)
-        torch.cuda.synchronize()
-        reps = 100
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            tman.tman_mpgemm(ps, pblob, px, NP, py, None)
-        torch.cuda.synchronize()
-        sec = (time.perf_counter() - t0) / reps
-        sub = slice(0, spec.M, 8)
-        c0 = time.perf_counter()
-        Y, used = oracle.matmul(np.ascontiguousarray(q[sub]), np.ascontiguousarray(sc[sub]), np.ascontiguousarray(z[sub]),
-                                xh, pw.bits, pw.group, return_threads=True)
-        cpu_t = (time.perf_counter() - c0) * 8
-        err = float(oracle.row_relative_error(py.cpu().numpy().astype(np.float64)[:, sub], Y).max())
+        sec = timed_steps(torch, lambda i: tman.tman_mpgemm(ps, pblob, px, NP, py, None), 40, 100)
         tf = 2.0 * NP * spec.M * spec.K / sec / 1e12
-        emit([f"{pw.name} N={NP}", f"{sec * 1e6:.1f}", f"{tf:.0f} TFLOP/s", f"{tf / MFMA_F16_PEAK_TFLOPS:.1%}",
-              f"{err:.2e} (every 8th row)", f"{cpu_t * 1e3:.0f} (8 x the sampled rows)", used, f"{cpu_t / sec:.0f}x"])
+        err, rows = prefill_error(oracle, q, sc, z, xh, py, pw)
+        add(f"{pw.name}: {spec.M}x{spec.K} uint4 g64, N={NP}", sec, tf, "TFLOP/s", MFMA_F16_PEAK_TFLOPS, err,
+            f"{len(rows)} whole tokens (first, last, tile edges, seeded picks)")
+    return out
+
+
+def prefill_error(oracle, q, sc, z, xh, py, pw):
+    """Row-normalised error of a seeded sample of whole tokens (all output features of each) against the oracle."""
+    NP = xh.shape[0]
+    rng = np.random.default_rng(NP)
+    rows = sorted(set([0, 1, 127, 128, NP // 2, NP - 129, NP - 128, NP - 1]) | set(rng.integers(0, NP, 16).tolist()))
+    rows = [r for r in rows if 0 <= r < NP]
+    Y = oracle.matmul(q, sc, z, xh[rows], pw.bits, pw.group)
+    y = py[rows].cpu().numpy().astype(np.float64)
+    return float(oracle.row_relative_error(y, Y).max()), rows
+
+
+
+def print_table(out):
+    rows = [("config", "GPU time (us)", "rate", "of vendor peak", "max err", "checked")]
+    rows.append((out["config"]["workload"][:60] + "...", f"{out['ms_per_step'] * 1e3:.2f}", f"{out['value']:.0f} GB/s",
+                 f"{out['value'] / HBM_PEAK_GBS:.1%}", f"{out['max_err']:.2e}", "all outputs of copy 0"))
+    if "prefill" in out:
+        p = out["prefill"]
+        rows.append((p["config"]["workload"], f"{p['ms_per_call'] * 1e3:.1f}", f"{p['value']:.0f} TFLOP/s",
+                     f"{p['roofline']['frac']:.1%}", f"{p['max_err']:.2e}", p["checked"]))
+    for c in out.get("configs", []):
+        rows.append((c["workload"], f"{c['us']:.2f}", f"{c['rate']:.0f} {c['unit']}", f"{c['frac']:.1%}",
+                     f"{c['max_err']:.2e}", c["checked"]))
+    for r in rows:
+        print("| " + " | ".join(r) + " |", file=sys.stderr)
+    if "cpu_baseline" in out:
+        c = out["cpu_baseline"]
+        print(f"oracle on the host: {c['value']} {c['unit']} on {c['cores']} cores ({c['sample']})", file=sys.stderr)
 
 
 def context_figures(args, torch, dev, job, n_inst):
     """The step on one copy of the layer set (cache-resident), as two launches, and a plain device copy."""
     x_calls, lut_calls, gemv_calls, stream = job["x_calls"], job["lut_calls"], job["gemv_calls"], job["stream"]
     weight_bytes_per_step = job["weight_bytes_per_step"]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        x_calls[0](stream)
-    torch.cuda.synchronize()
-    hot_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
+    steps = max(args.steps, 500)
+    hot_value = weight_bytes_per_step / timed_steps(torch, lambda i: x_calls[0](stream), 100, steps) / 1e9
+
     # the same step as two launches (table precompute kernel, then the lookup kernel reading its tables)
-    for i in range(args.warmup):
+    def two(i):
         lut_calls[i % n_inst](stream)
         gemv_calls[i % n_inst](stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        lut_calls[i % n_inst](stream)
-        gemv_calls[i % n_inst](stream)
-    torch.cuda.synchronize()
-    two_launch_value = weight_bytes_per_step / ((time.perf_counter() - t0) / args.steps) / 1e9
+
+    two_launch_value = weight_bytes_per_step / timed_steps(torch, two, 100, steps) / 1e9
     cp_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     cp_dst = torch.empty_like(cp_src)
     cp_dst.copy_(cp_src)
@@ -305,10 +317,6 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    if args.table:
-        run_table(args, torch, tman, synth, dev)
-        return
-
     w = synth.WORKLOADS[args.workload]
     n_inst = args.instances or w.instances
     N = 1
@@ -317,13 +325,20 @@ def main():
     lut_calls, gemv_calls, x_calls, stream = job["lut_calls"], job["gemv_calls"], job["x_calls"], job["stream"]
     events = []
 
-    def step(i, record):
-        # activations in, outputs out: the table precompute and the lookups of all five GEMVs in one launch
+    # One step = one token through a 32-layer decoder of this layer set: the 32 copies in turn, one launch each
+    # (activations in, outputs out: the table precompute and the lookups of all five GEMVs of a layer set).
+    launches_per_step = n_inst
+
+    def launch(j, record):
         if record:
             e = torch.cuda.Event(enable_timing=True)
             e.record()
-            events.append((i, e))
-        x_calls[i % n_inst](stream)
+            events.append((j, e))
+        x_calls[j % n_inst](stream)
+
+    def step(i, timed):
+        for j in range(i * launches_per_step, (i + 1) * launches_per_step):
+            launch(j, timed and j % args.event_every == 0)
 
     if args.calibration_copy:
         src = torch.full((256 << 20,), 7, dtype=torch.uint8, device=dev)
@@ -333,18 +348,23 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    for i in range(args.preroll):  # clocks and caches to their steady state, before the declared warm-up
+        launch(i, False)
+    torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i, False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, i % args.event_every == 0)
+        step(i, True)
     e = torch.cuda.Event(enable_timing=True)
     e.record()
-    events.append((args.steps, e))
+    events.append((args.steps * launches_per_step, e))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     sec_per_step = (t1 - t0) / args.steps
+    weight_bytes_per_launch = weight_bytes_per_step
+    weight_bytes_per_step = weight_bytes_per_launch * launches_per_step
     value = weight_bytes_per_step / sec_per_step / 1e9
 
     # dominant kernel: the table-lookup GEMV (one launch per step covers the whole layer set); its average
@@ -353,7 +373,7 @@ def main():
     n_launch = sum(n for n, _ in runs)
     avg_launch_s = sum(ms for _, ms in runs) / 1e3 / n_launch
     gemv_ms = sorted(ms / n for n, ms in runs)  # per-launch averages of the runs
-    bytes_per_launch = weight_bytes_per_step
+    bytes_per_launch = weight_bytes_per_launch
     achieved = bytes_per_launch / avg_launch_s / 1e9
     roofline = {
         "bound": "hbm", "kernel": "mpgemv_x_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -366,19 +386,28 @@ def main():
 
     # context figures (not the headline): the same step on ONE copy of the layer set (63 MB: served by the
     # 256 MB Infinity Cache), the bit-plane bytes alone, and what a plain device copy moves on this machine
-    codes_bytes = sum(s.M * s.K * w.bits // 8 for s in shapes)
+    codes_bytes = sum(s.M * s.K * w.bits // 8 for s in shapes) * launches_per_step
     context = {}
     if not args.no_context:
         context = context_figures(args, torch, dev, job, n_inst)
 
+    # the same step on copy 0 against the fp64 oracle, every output of the five GEMVs
+    import oracle
+
+    oracle.build()
+    max_err, _, _ = decode_error(torch, synth, oracle, w, job, N)
+
     out = {
         "metric": "decode mpGEMV weight GB/s", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "max_err": float(f"{max_err:.3e}"), "tolerance": 2e-3,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec_per_step * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: 7B-style layer set (qkv 12288x4096, o 4096x4096, gate/up 11008x4096, "
-                               f"down 4096x11008), uint{w.bits} g{w.group}, N=1 decode, {n_inst} rotating copies; "
-                               f"step = one launch: every workgroup builds the lookup tables of its K segment "
-                               f"from the {len(acts)} activations, then does its lookups",
+        "config": {"workload": f"{w.name}: decode of one token (N=1) through {n_inst} layers of the 7B-style layer set "
+                               f"(qkv 12288x4096, o 4096x4096, gate/up 11008x4096, down 4096x11008), uint{w.bits} "
+                               f"g{w.group}, every layer with weights of its own ({weight_bytes_per_step / 1e9:.2f} GB per "
+                               f"step); one launch per layer: every workgroup builds the lookup tables of its K "
+                               f"segment from the layer's {len(acts)} activations, then does its lookups",
+                   "launches_per_step": launches_per_step, "us_per_launch": round(sec_per_step / launches_per_step * 1e6, 3),
                    "weight_bytes_per_step": int(weight_bytes_per_step), "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
                    "codes_only_GBs": round(value * codes_bytes / weight_bytes_per_step, 1), **context},
         "roofline": roofline,
@@ -411,8 +440,11 @@ def main():
         avg_ms = sum(ts) / len(ts)
         flops = 2.0 * NP * spec.M * spec.K
         tf = flops / (avg_ms / 1e3) / 1e12
+        qh, sh, zh = synth.layer_tensors(pw, 0, 0)
+        perr, prow = prefill_error(oracle, qh, sh, zh, synth.activation(pw, 0, 0, NP), py, pw)
         out["prefill"] = {
             "metric": "prefill mpGEMM TFLOPS", "value": round(tf, 1), "unit": "TFLOP/s",
+            "max_err": float(f"{perr:.3e}"), "checked": f"{len(prow)} whole tokens",
             "config": {"workload": f"{pw.name}: {spec.M}x{spec.K} uint4 g64, N={NP}"},
             "ms_per_call": round(avg_ms, 4), "fastest_run_ms_per_call": round(ts[0], 4),
             "roofline": {"bound": "mfma", "kernel": "mpgemm_kernel", "achieved": round(tf, 1),
@@ -421,11 +453,13 @@ def main():
         }
         del pblob, px, py
 
+    # ------------------------------------------------------------------ every other BASELINE configuration
+    del job, lut_calls, gemv_calls, x_calls
+    if not args.no_configs:
+        out["configs"] = other_configs(args, torch, tman, synth, oracle, dev)
+
     # ------------------------------------------------------------------ CPU oracle on the host cores
     if not args.no_cpu_baseline:
-        import oracle
-
-        oracle.build()
         done_bytes, cpu_t, cores, used = 0, 0.0, os.cpu_count(), 1
         sample = []
         inst = 0
@@ -449,7 +483,9 @@ def main():
                       f"dequantize-then-multiply; weight bytes counted as for the GPU",
         }
 
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
+    if args.table:
+        print_table(out)
 
 
 if __name__ == "__main__":
