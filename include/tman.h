@@ -34,7 +34,8 @@ typedef enum tman_status {
     TMAN_ERR_SHAPE = -4,     /* M < 1, K < 1, K % group != 0, N out of range, flags/zeros mismatch */
     TMAN_ERR_WORKSPACE = -5, /* workspace missing or smaller than the *_workspace_bytes query */
     TMAN_ERR_ALIGN = -6,     /* a pointer is not 16-byte aligned */
-    TMAN_ERR_LAUNCH = -7     /* the HIP runtime reported an error when launching */
+    TMAN_ERR_LAUNCH = -7,    /* the HIP runtime reported an error when launching */
+    TMAN_ERR_HEADER = -8     /* a packed blob's header disagrees with the shape it is used with */
 } tman_status;
 
 #define TMAN_FLAG_HAS_ZERO 1 /* weights carry a per-group zero point (affine form) */
@@ -168,12 +169,41 @@ int tman_mpgemv_x_batch_prepare(int32_t count, const tman_shape_t *shapes, const
 int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t *shapes, const void *desc, void *stream);
 
 /*
+ * How a one-token batch is cut into work for the resident workgroups (host only, informational; the same
+ * cut tman_mpgemv_x_batch_prepare makes with max_slots = 3 x the compute units of the device).  The tile
+ * blocks of the batch (GEMV after GEMV, row block after row block, K tile after K tile; tile block = 64 rows
+ * x 128 columns) form one sequence that is cut into at most `max_slots` slots of nearly equal length, row
+ * blocks of at most 40 tiles staying whole where the slot length allows.  `slots` receives six numbers per
+ * slot: GEMV and linear tile index where the slot starts, its tile count, the index of its first interval
+ * among the intervals of that row block, and the number of intervals of the row blocks of its first and of
+ * its last interval (an interval = what a slot holds of one row block).  Returns the number of slots, 0 on
+ * invalid arguments (max_slots in [1, 4096]).
+ */
+int32_t tman_mpgemv_x_plan(int32_t count, const tman_shape_t *shapes, int32_t max_slots, int32_t *slots);
+
+/*
+ * Packed blobs carry a 128-byte header (shape, tile geometry, layout version).
+ * tman_check_packed compares it with `shape` on the host: it copies the header back on `stream` and WAITS for
+ * the stream (the one blocking call of the library; meant for load time).  TMAN_ERR_HEADER on disagreement.
+ * The compute calls also check on the device: tman_mpgemv, tman_mpgemv_x and tman_mpgemm at kernel entry, the
+ * batch forms when their descriptor table is prepared.  A GEMV whose blob disagrees with its shape is
+ * skipped (its y is left untouched) and TMAN_ERR_HEADER is stored in a status word in device memory that
+ * tman_device_status returns and clears (it waits for `stream`; TMAN_OK when nothing was reported).  The
+ * device-side check protects results, not memory: the kernels size their reads from `shape`, so a blob that is
+ * SMALLER than the shape says must be caught with tman_check_packed before it is used.
+ */
+int tman_check_packed(const tman_shape_t *shape, const void *packed, void *stream);
+int tman_device_status(void *stream);
+
+/*
  * Prefill mpGEMM (Sec. 4.1 "Fused LUT-based dequantization", Sec. 4.2): bit-planes are repacked to
  * codes (level 1), each code is looked up in its quantization block's table
  * D[c] = fp16((c - zero) * scale) (level 2; sign form fp16((2c - 1) * scale)), and the fp16 weights
  * feed the matrix cores with fp32 accumulation.
  *   x : fp16 [N][K], any N >= 1;   y : fp16 [N][M]
- *   workspace : tman_mpgemm_workspace_bytes(shape, N) bytes (may be 0, then NULL is accepted)
+ *   workspace : tman_mpgemm_workspace_bytes(shape, N) bytes.  The query returns 0 for every shape today (the
+ *               kernel needs no scratch memory); the arguments are kept so that a later split of K across
+ *               workgroups does not change the signature.  NULL / 0 is accepted.
  */
 int tman_mpgemm(const tman_shape_t *shape, const void *packed, const void *x, int32_t N, void *y, void *workspace,
                 size_t workspace_bytes, void *stream);

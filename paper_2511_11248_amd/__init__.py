@@ -18,6 +18,9 @@ from .api import (  # noqa: F401
     tman_mpgemv,
     tman_mpgemm,
     tman_noalloc_init,
+    tman_check_packed,
+    tman_device_status,
+    tman_mpgemv_x_plan,
     tman_mpgemv_noalloc,
     tman_mpgemm_tile_rows,
     tman_mpgemv_batch_desc_bytes,

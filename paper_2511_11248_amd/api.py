@@ -90,6 +90,12 @@ def _load():
         L.tman_mpgemm.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
         L.tman_mpgemm_tile_rows.restype = C.c_int32
         L.tman_mpgemm_tile_rows.argtypes = [sp, C.c_int32]
+        L.tman_check_packed.restype = C.c_int
+        L.tman_check_packed.argtypes = [sp, vp, vp]
+        L.tman_device_status.restype = C.c_int
+        L.tman_device_status.argtypes = [vp]
+        L.tman_mpgemv_x_plan.restype = C.c_int32
+        L.tman_mpgemv_x_plan.argtypes = [C.c_int32, sp, C.c_int32, C.POINTER(C.c_int32)]
         L.tman_noalloc_init.restype = C.c_int
         L.tman_noalloc_init.argtypes = []
         L.tman_mpgemv_noalloc.restype = C.c_int
@@ -178,6 +184,25 @@ def tman_mpgemv(shape: Shape, packed, lut, N: int, y, workspace, stream=None) ->
     wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
     _check(_load().tman_mpgemv(C.byref(shape.c()), _ptr(packed), _ptr(lut), N, _ptr(y), _ptr(workspace), wb,
                                _stream(stream)), "tman_mpgemv")
+
+
+def tman_check_packed(shape: Shape, packed, stream=None) -> int:
+    """Status of the host-side header check (0 or TMAN_ERR_HEADER = -8); waits for the stream."""
+    return int(_load().tman_check_packed(C.byref(shape.c()), _ptr(packed), _stream(stream)))
+
+
+def tman_device_status(stream=None) -> int:
+    """Returns and clears the device status word (0, or -8 when a kernel met a blob with a foreign header)."""
+    return int(_load().tman_device_status(_stream(stream)))
+
+
+def tman_mpgemv_x_plan(shapes, max_slots: int):
+    """The cut of a one-token batch into slots: list of (gemv, first, count, pidx0, nparts_first, nparts_last)."""
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    buf = (C.c_int32 * (6 * max_slots))()
+    k = int(_load().tman_mpgemv_x_plan(n, cs, max_slots, buf))
+    return [tuple(buf[6 * i:6 * i + 6]) for i in range(k)]
 
 
 def tman_noalloc_init() -> None:

@@ -58,6 +58,7 @@ struct GemmArgs {
     _Float16* y;
     int M, N, K, n_row_blocks, n_ktiles;
     int m_tiles, n_tiles;
+    int* status;  // the library's status word
 };
 
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
@@ -242,6 +243,11 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
     const int mt = (slot / a.n_tiles) * kXcds + xcd, nt = slot % a.n_tiles;
     if (mt >= a.m_tiles) return;
+    // a blob packed for another shape or layout: leave y alone and say so
+    if (!header_matches(a.tiles, a.M, a.K, B, GQ, HZ ? 1 : 0)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) report_header_mismatch(a.status);
+        return;
+    }
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -625,6 +631,8 @@ int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, voi
     a.n_row_blocks = L.n_row_blocks;
     a.n_ktiles = L.n_ktiles;
     a.m_tiles = a.n_tiles = 0;
+    a.status = device_status_word();
+    if (!a.status) return TMAN_ERR_LAUNCH;
     if (L.bits == 1) return L.has_zero ? launch_group<1, true>(L.group, a, st) : launch_group<1, false>(L.group, a, st);
     if (L.bits == 2) return launch_group<2, true>(L.group, a, st);
     return launch_group<4, true>(L.group, a, st);

@@ -25,25 +25,12 @@
 // All GEMVs of a decode step can share one launch (descriptor table), so the machine is filled even
 // though one layer alone is too small.
 //
-// Two kernels follow.  mpgemv_kernel serves 1 to 8 tokens and reads the tables tman_build_lut made
-// (Sec. 5: the precompute as a kernel of its own, shared by the layers fed from one activation).
-// mpgemv_x_kernel serves one token and builds the tables of its K segment itself, in LDS, from the
-// activations: the same lookups, but a decode step is a single launch and no table ever reaches memory.
-#include <hip/hip_fp16.h>
-
-#include <type_traits>
-
-#include "tman_internal.h"
+// mpgemv_kernel serves 1 to 8 tokens and reads the tables tman_build_lut made (Sec. 5: the precompute as a
+// kernel of its own, shared by the layers fed from one activation).  The one-token kernel that builds its
+// tables itself is in tman_mpgemv_x.hip.
+#include "tman_gemv_device.h"
 
 namespace tman {
-
-typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int kWaves = 4;  // waves per workgroup
 
 // ---------------------------------------------------------------------------------------------
 // host-side planning
@@ -64,15 +51,6 @@ GemvPlan plan_gemv(const Layout& L, int N) {
     const int np = padded_tokens(N);
     // with four or eight tokens a tile takes about twice as long: shorter segments, more workgroups (measured)
     return plan_segments(L, np, np >= 4 ? kGemvManyTokensSegmentTiles : kGemvSegmentTiles);
-}
-
-// Segments of the kernel that builds its own tables (measured on the 7B and 3.8B layer sets): a K that one
-// workgroup can take whole - up to 32 tiles and about 80 KB of packed weights per row block - is one segment,
-// which spares the exchange of partial sums; a longer K is cut into segments of at most 24 tiles.
-GemvPlan plan_gemv_x(const Layout& L) {
-    int whole = 81920 / L.tile_bytes;
-    if (whole > kGemvXSegmentTiles) whole = kGemvXSegmentTiles;
-    return plan_segments(L, 1, L.n_ktiles <= whole ? whole : kGemvXLongSegmentTiles);
 }
 
 static void fill_desc_plan(GemvDesc& d, const Layout& L, const GemvPlan& p, const void* packed, const void* lut, int N,
@@ -98,36 +76,8 @@ void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut
     fill_desc_plan(d, L, plan_gemv(L, N), packed, lut, N, y, workspace, wg_begin);
 }
 
-void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x, void* y, void* workspace) {
-    fill_desc_plan(d, L, plan_gemv_x(L), packed, x, 1, y, workspace, 0);
-    d.lut_s = nullptr;
-}
-
 // ---------------------------------------------------------------------------------------------
 // device side
-
-template <int B, int NP, int GQ, bool HZ>
-struct GemvCfg {
-    static constexpr int CH = kKTile / B;    // weights per 16-byte chunk
-    static constexpr int GPT = kKTile / GQ;  // quantization groups per tile
-    static constexpr int MSZ = HZ ? 4 : 2;
-    static constexpr int MPL = GPT * MSZ;    // group-parameter bytes per lane and tile
-    static constexpr int TB = B * 1024 + 64 * MPL;
-    static constexpr int T_BYTES = kTableBytesPerKTile * NP;
-    static constexpr int S_FLOATS = GPT * NP;
-    static constexpr int SLOT = T_BYTES + 256;  // table slice + group sums, per wave (multiple of 256)
-    // tile blocks in flight per wave.  Measured: more do not help (the waves of a compute unit together
-    // keep enough requests in flight) and cost time.
-    static constexpr int D = NP >= 4 ? 1 : (B == 4 ? 1 : (B == 2 ? 2 : 3));
-};
-
-template <int B, int NP, int MPL>
-struct Stage {
-    u32x4 c[B];                    // bit-plane chunks
-    uint32_t meta[(MPL + 3) / 4];  // scales / zeros of the lane's groups
-    u32x4 tt[NP];                  // this lane's 16 bytes of each 1 KB of the table slice
-    float sv;                      // one group sum (lanes < S_FLOATS)
-};
 
 // kernel arguments: the descriptor itself for a single GEMV, the device table for a batch
 template <bool SINGLE>
@@ -135,126 +85,14 @@ struct KernelArgs;
 template <>
 struct KernelArgs<true> {
     GemvDesc single;
-    int n_gemv;  // 1
+    int n_gemv;   // 1
+    int* status;  // the library's status word
 };
 template <>
 struct KernelArgs<false> {
     const GemvDesc* descs;
     int n_gemv;
 };
-
-__device__ __forceinline__ uint32_t word_of(const u32x4& v, int w) {
-    return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w;
-}
-
-// Lanes of one wave exchange data through the wave's private LDS slot.  The hardware executes the
-// LDS operations of a wave in order; this keeps the compiler from moving them across the exchange.
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-}
-
-__device__ __forceinline__ float half_bits_to_float(uint32_t bits16) {
-    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits16);
-}
-
-// values every lane agrees on, made visibly scalar for the compiler
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-template <typename T>
-__device__ __forceinline__ T* uniform(T* p) {
-    const uint64_t v = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return reinterpret_cast<T*>(((uint64_t)hi << 32) | lo);
-}
-
-// explicit address spaces: descriptor pointers come out of memory as generic pointers, which would
-// turn every access into a flat instruction
-template <typename T>
-using global_ptr = const T __attribute__((address_space(1)))*;
-template <typename T>
-using lds_ptr = T __attribute__((address_space(3)))*;
-
-// wave-uniform base pointer + 32-bit per-lane byte offset: the form that needs no per-lane
-// 64-bit address arithmetic
-template <typename T>
-__device__ __forceinline__ T load_global(const uint8_t* base, uint32_t off) {
-    global_ptr<uint8_t> b = reinterpret_cast<global_ptr<uint8_t>>(reinterpret_cast<uintptr_t>(base));
-    return *reinterpret_cast<global_ptr<T>>(b + off);
-}
-template <typename T>
-__device__ __forceinline__ T load_lds(uint32_t addr) {
-    return *reinterpret_cast<lds_ptr<const T>>(static_cast<uintptr_t>(addr));
-}
-template <typename T>
-__device__ __forceinline__ void store_lds(uint32_t addr, T v) {
-    *reinterpret_cast<lds_ptr<T>>(static_cast<uintptr_t>(addr)) = v;
-}
-
-// byte K of x, zero extended, in one full-rate VALU instruction
-template <int K>
-__device__ __forceinline__ uint32_t byte_of(uint32_t x) {
-    uint32_t r;
-    if constexpr (K == 0)
-        asm("v_and_b32 %0, 0xff, %1" : "=v"(r) : "v"(x));
-    else if constexpr (K == 3)
-        asm("v_lshrrev_b32 %0, 24, %1" : "=v"(r) : "v"(x));
-    else if constexpr (K == 1)
-        asm("v_bfe_u32 %0, %1, 8, 8" : "=v"(r) : "v"(x));
-    else
-        asm("v_bfe_u32 %0, %1, 16, 8" : "=v"(r) : "v"(x));
-    return r;
-}
-
-// a uniform float the compiler cannot constant-fold, so x * w + acc with fp16 x stays one
-// mixed-precision FMA also for w == 1
-__device__ __forceinline__ float opaque(float v) {
-    asm("" : "+s"(v));
-    return v;
-}
-
-// Buffer resource over a wave-uniform base: loads then take a 32-bit per-lane offset (constant for
-// the whole kernel) plus a scalar offset (the tile), so streaming costs no address arithmetic.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-constexpr int kStreamAux = 2;  // non-temporal: weights are read once, keep them from evicting the tables in L2
-__device__ __forceinline__ rsrc_t make_rsrc(const uint8_t* base, uint32_t bytes = 0xFFFFFFFFu) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, bytes, 0x00020000);
-}
-
-// The three streams a wave reads: its row block's tile blocks, the table slices and the group sums.
-struct Streams {
-    const uint8_t *w, *t, *s;
-    uint32_t w_bytes, t_bytes, s_bytes;
-};
-
-// Requests the weights of tile kt: bit-plane chunks and group parameters of the lane's row.  With `live`
-// false nothing is fetched and the stage reads as zeros: the caller needs no branch around the request, so
-// a tile's lookups and the next request stay one basic block.
-template <int B, int NP, int GQ, bool HZ>
-__device__ __forceinline__ void issue_weights(Stage<B, NP, GemvCfg<B, NP, GQ, HZ>::MPL>& s, const Streams& src, bool live,
-                                              int kt, int lane) {
-    using Cfg = GemvCfg<B, NP, GQ, HZ>;
-    const rsrc_t rw = make_rsrc(src.w, live ? src.w_bytes : 0u);
-    const int so = kt * Cfg::TB;  // scalar offset of the tile block inside the row block
-#pragma unroll
-    for (int v = 0; v < B; ++v) s.c[v] = __builtin_amdgcn_raw_buffer_load_b128(rw, v * 1024 + lane * 16, so, kStreamAux);
-    const int mo = B * 1024 + lane * Cfg::MPL;
-    if constexpr (Cfg::MPL == 2) {
-        s.meta[0] = __builtin_amdgcn_raw_buffer_load_b16(rw, mo, so, kStreamAux);
-    } else if constexpr (Cfg::MPL == 4) {
-        s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rw, mo, so, kStreamAux);
-    } else if constexpr (Cfg::MPL == 8) {
-        u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rw, mo, so, kStreamAux);
-        s.meta[0] = v.x;
-        s.meta[1] = v.y;
-    } else {
-        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, mo, so, kStreamAux);
-        s.meta[0] = v.x;
-        s.meta[1] = v.y;
-        s.meta[2] = v.z;
-        s.meta[3] = v.w;
-    }
-}
 
 // Requests tile kt: its weights, its slice of the lookup tables and its group sums (same rule for `live`).
 template <int B, int NP, int GQ, bool HZ>
@@ -502,6 +340,14 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
     const int n_seg = uniform(d.n_seg), n_ktiles = uniform(d.n_ktiles);
     const int wg_local = (int)blockIdx.x;
     if (wg_local >= uniform(d.n_row_blocks) * n_seg) return;
+    if constexpr (SINGLE) {
+        // a blob packed for another shape or layout: leave y alone and say so (a batch is checked when its
+        // descriptor table is written, which empties the descriptor of such a GEMV)
+        if (!header_matches(uniform(d.tiles), uniform(d.M), uniform(d.K), B, GQ, HZ ? 1 : 0)) {
+            if (wg_local == 0 && threadIdx.x == 0) report_header_mismatch(a.status);
+            return;
+        }
+    }
     const int rb = wg_local / n_seg, seg = wg_local % n_seg;
     const int seg_tiles = uniform(d.seg_tiles);
     const int k0 = seg * seg_tiles;
@@ -568,217 +414,6 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_kernel(KernelArgs<SINGLE> 
 }
 
 // ---------------------------------------------------------------------------------------------
-// One token, tables built in the kernel.
-//
-// With a single token the tables of a whole K segment (at most 32 tiles = 1024 tables = 32 KB) fit in LDS
-// next to three or more other workgroups.  The workgroup builds them itself from the activations of its
-// segment (at most 8 KB) while its first weight tiles are on their way, so a decode step needs no launch for
-// the table precompute, no table traffic between the two kernels, and no per-tile copy of a table
-// slice into LDS.  The entries have the values build_lut_kernel computes (fp32 sums in ascending order,
-// one rounding to fp16), as have the group sums (same tree of additions).
-//
-// A lookup address is tile base | index byte: one v_perm_b32 takes byte k of the prepared index word as
-// byte 0 and bytes 1..3 of the tile's table base (a multiple of 1024), the table's place inside the
-// tile is the immediate offset of the LDS load.  One instruction per lookup, as in the kernel above.
-
-__device__ __forceinline__ uint32_t index_into(uint32_t idx_word, uint32_t base, uint32_t selector) {
-    uint32_t r;
-    asm("v_perm_b32 %0, %1, %2, %3" : "=v"(r) : "v"(idx_word), "v"(base), "s"(selector));
-    return r;
-}
-
-// Sum over blocks of W consecutive lanes (W = 8, 16 or 32), every lane of a block receiving the block's sum.
-// A butterfly: at each step a lane adds the sum of the neighbouring sub-block, which all lanes of that
-// sub-block hold, so the mirror permutations of DPP serve as well as an exchange with lane ^ d.
-template <int CTRL>
-__device__ __forceinline__ float add_dpp(float v) {
-    return v + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-template <int W>
-__device__ __forceinline__ float sum_over_lanes(float v) {
-    v = add_dpp<0xB1>(v);   // quad_perm [1,0,3,2]: lane ^ 1
-    v = add_dpp<0x4E>(v);   // quad_perm [2,3,0,1]: lane ^ 2
-    v = add_dpp<0x141>(v);  // row_half_mirror: the other quad of 8 lanes
-    if constexpr (W >= 16) v = add_dpp<0x140>(v);  // row_mirror: the other half of 16 lanes
-    if constexpr (W >= 32)  // lane ^ 16 (crosses DPP rows)
-        v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
-    return v;
-}
-
-// Lookups of one tile block; `tbase` is the LDS address of the tile's 32 tables, `sbase` of its group sums.
-template <int B, int GQ, bool HZ>
-__device__ __forceinline__ void consume_weights(const Stage<B, 1, GemvCfg<B, 1, GQ, HZ>::MPL>& s, uint32_t tbase,
-                                                uint32_t sbase, const uint32_t (&sel)[4], const float (&pw)[B],
-                                                float& y) {
-    using Cfg = GemvCfg<B, 1, GQ, HZ>;
-    constexpr uint32_t NIB = 0x1E1E1E1Eu;  // index * 2 bytes, one per byte
-    constexpr int TSTRIDE = 32;
-    constexpr int W = 4 * B;
-    constexpr int WPG = (GQ / 32) * B;
-    auto fetch = [&](int wi, _Float16 (&e)[8]) {
-        const int kb32 = wi / B, i = wi % B;
-        const int v = (kb32 * 32) / Cfg::CH;
-        const int ksub = ((kb32 * 32) % Cfg::CH) / 32;
-        const int tb = (kb32 * 8) * TSTRIDE;
-        const uint32_t w = word_of(s.c[v], ksub * B + i);
-        const uint32_t xe = (w << 1) & NIB;
-        const uint32_t xo = (w >> 3) & NIB;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            e[2 * k] = load_lds<_Float16>(index_into(xe, tbase, sel[k]) + (tb + (2 * k) * TSTRIDE));
-            e[2 * k + 1] = load_lds<_Float16>(index_into(xo, tbase, sel[k]) + (tb + (2 * k + 1) * TSTRIDE));
-        }
-    };
-    _Float16 e[2][8];
-    float a = 0.f;
-    fetch(0, e[0]);
-#pragma unroll
-    for (int wi = 0; wi < W; ++wi) {
-        if (wi + 1 < W) fetch(wi + 1, e[(wi + 1) & 1]);
-        if (wi % WPG == 0) a = 0.f;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) a = fmaf(pw[wi % B], (float)e[wi & 1][u], a);
-        if (wi % WPG == WPG - 1) {
-            const int gi = wi / WPG;
-            const int mo = gi * Cfg::MSZ;
-            const uint32_t mw = s.meta[mo / 4];
-            const float sc = half_bits_to_float((mo % 4) ? (mw >> 16) : (mw & 0xffffu));
-            const float gs = load_lds<float>(sbase + gi * 4);
-            if constexpr (HZ) {
-                const float z = half_bits_to_float(mw >> 16);
-                y = fmaf(sc, fmaf(-z, gs, a), y);
-            } else {
-                y = fmaf(sc, fmaf(2.f, a, -gs), y);
-            }
-        }
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-    }
-}
-
-template <int B, int GQ, bool HZ, bool SINGLE>
-__global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE> a) {
-    using Cfg = GemvCfg<B, 1, GQ, HZ>;
-    constexpr int D = Cfg::D;
-    constexpr int TPG = GQ / kLutGroup;  // tables per quantization group: 8, 16 or 32 consecutive lanes
-    // LDS of a workgroup: the tables of its segment, their group sums, the four partial sums of each row.  The
-    // launch sizes it for the longest segment among its GEMVs, so short segments leave room for more workgroups.
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds_x[];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    float pw[B];
-#pragma unroll
-    for (int i = 0; i < B; ++i) pw[i] = opaque((float)(1 << i));
-
-    const int g = SINGLE ? 0 : (int)blockIdx.y;
-    const GemvDesc& d = desc_of<SINGLE>(a, g);
-    const int n_seg = uniform(d.n_seg), n_ktiles = uniform(d.n_ktiles);
-    const int wg_local = (int)blockIdx.x;
-    if (wg_local >= uniform(d.n_row_blocks) * n_seg) return;
-    // (the division runs on the vector unit: bring its results back to scalar registers, or every buffer
-    // resource derived from them is taken for lane dependent)
-    const int rb = uniform(wg_local / n_seg), seg = uniform(wg_local % n_seg);
-    const int seg_tiles = uniform(d.seg_tiles);
-    const int k0 = seg * seg_tiles;
-    const int k1 = min(k0 + seg_tiles, n_ktiles);
-    const int per_wave = (k1 - k0 + kWaves - 1) / kWaves;
-    const int t0 = min(k0 + wave * per_wave, k1);
-    const int t1 = min(t0 + per_wave, k1);
-    Streams src;
-    src.w = uniform(d.tiles) + (size_t)rb * n_ktiles * Cfg::TB;
-    src.t = src.s = nullptr;
-    src.w_bytes = (uint32_t)(n_ktiles * Cfg::TB);
-    src.t_bytes = src.s_bytes = 0;
-
-    const uint32_t lt = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr<uint8_t>)lds_x));
-    const uint32_t ls = lt + (uint32_t)seg_tiles * kTableBytesPerKTile;  // group sums follow the tables
-    const uint32_t lr = ls + (uint32_t)seg_tiles * Cfg::GPT * 4;         // then the partial sums [wave][row]
-
-    // first weight tiles on their way before anything else
-    Stage<B, 1, Cfg::MPL> st[D] = {};
-#pragma unroll
-    for (int s = 0; s < D; ++s) issue_weights<B, 1, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
-
-    // tables and group sums of the segment: thread -> tables tid, tid + 256, ... (x beyond K reads as zero).
-    // The range check of a buffer load covers the per-lane offset only, not the scalar offset, so the resource
-    // starts at the segment's first activation and ends with x: K * 2 bytes less the segment's start.
-    {
-        const uint32_t x_start = (uint32_t)(k0 * kKTile * 2);  // k0 < n_ktiles, so this lies inside x
-        const rsrc_t rx = make_rsrc(uniform(d.lut_t) + x_start, (uint32_t)uniform(d.K) * 2u - x_start);
-        const int n_tab = (k1 - k0) * kTablesPerKTile;
-        constexpr int kPasses = kGemvXSegmentTiles * kTablesPerKTile / (kWaves * 64);
-        static_assert(kPasses * kWaves * 64 == kGemvXSegmentTiles * kTablesPerKTile, "whole passes");
-        u32x2 xv[kPasses];  // all requests first (a pass beyond the segment reads activations nobody uses)
-#pragma unroll
-        for (int i = 0; i < kPasses; ++i)
-            xv[i] = __builtin_amdgcn_raw_buffer_load_b64(rx, (i * kWaves * 64 + tid) * 8, 0, 0);
-#pragma unroll
-        for (int i = 0; i < kPasses; ++i) {
-            if (i * kWaves * 64 >= n_tab) break;
-            const int j = i * kWaves * 64 + tid;
-            // (copy the elements out first: a bit cast applied directly to a vector element reads element 0)
-            const uint32_t w01 = xv[i].x, w23 = xv[i].y;
-            const half2_t x01 = __builtin_bit_cast(half2_t, w01), x23 = __builtin_bit_cast(half2_t, w23);
-            const float v[4] = {(float)x01[0], (float)x01[1], (float)x23[0], (float)x23[1]};
-            // entry p = sum of the v[t] with bit t of p set, added in ascending t
-            float e[16];
-            e[0] = 0.f;
-            e[1] = v[0];
-            e[2] = v[1];
-            e[3] = v[0] + v[1];
-#pragma unroll
-            for (int p = 4; p < 8; ++p) e[p] = p == 4 ? v[2] : e[p - 4] + v[2];
-#pragma unroll
-            for (int p = 8; p < 16; ++p) e[p] = p == 8 ? v[3] : e[p - 8] + v[3];
-            half8_t lo, hi;
-#pragma unroll
-            for (int p = 0; p < 8; ++p) {
-                lo[p] = (_Float16)e[p];
-                hi[p] = (_Float16)e[p + 8];
-            }
-            const float gs = sum_over_lanes<TPG>((v[0] + v[1]) + (v[2] + v[3]));
-            if (j < n_tab) {
-                store_lds<u32x4>(lt + j * 32, __builtin_bit_cast(u32x4, lo));
-                store_lds<u32x4>(lt + j * 32 + 16, __builtin_bit_cast(u32x4, hi));
-                if (j % TPG == 0) store_lds<float>(ls + (j / TPG) * 4, gs);
-            }
-        }
-    }
-    __syncthreads();
-
-    uint32_t sel[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) sel[k] = 0x03020100u | (uint32_t)(4 + k);
-    float y = 0.f;
-    for (int base = t0; base < t1; base += D) {
-#pragma unroll
-        for (int s = 0; s < D; ++s) {
-            const int t = base + s;
-            if (t < t1) {
-                {
-                    const int rem = t1 - t;
-                    if (rem >= 7) __builtin_amdgcn_s_setprio(3);
-                    else if (rem >= 5) __builtin_amdgcn_s_setprio(2);
-                    else if (rem >= 3) __builtin_amdgcn_s_setprio(1);
-                    else __builtin_amdgcn_s_setprio(0);
-                }
-                consume_weights<B, GQ, HZ>(st[s], lt + (t - k0) * kTableBytesPerKTile, ls + (t - k0) * Cfg::GPT * 4, sel, pw, y);
-                issue_weights<B, 1, GQ, HZ>(st[s], src, t + D < t1, t + D, lane);
-            }
-        }
-    }
-
-    store_lds<float>(lr + (wave * kRows + lane) * 4, y);
-    __syncthreads();
-    if (wave != 0) return;
-    y = ((load_lds<float>(lr + lane * 4) + load_lds<float>(lr + (kRows + lane) * 4)) +
-         load_lds<float>(lr + (2 * kRows + lane) * 4)) + load_lds<float>(lr + (3 * kRows + lane) * 4);
-    float yy[1] = {y};
-    finish_rows<1>(d, rb, seg, n_seg, lane, yy);
-}
-
-// ---------------------------------------------------------------------------------------------
 // launch
 
 template <int B, int NP, int GQ, bool HZ, bool SINGLE>
@@ -823,6 +458,8 @@ int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, v
     KernelArgs<true> a;
     fill_desc(a.single, L, packed, lut, N, y, workspace, 0);
     a.n_gemv = 1;
+    a.status = device_status_word();
+    if (!a.status) return TMAN_ERR_LAUNCH;
     return launch_format<true>(L.bits, L.has_zero, padded_tokens(N), L.group, a, plan_gemv(L, N).n_workgroups, st);
 }
 
@@ -834,64 +471,31 @@ int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc
     return launch_format<false>(bits, has_zero, padded_tokens(N), group, a, max_workgroups, st);
 }
 
-// LDS of a workgroup whose segment has `seg_tiles` tiles: tables, group sums (at most 4 per tile), partial sums
-static unsigned x_lds_bytes(int seg_tiles) {
-    return (unsigned)seg_tiles * (kTableBytesPerKTile + 4 * 4) + kWaves * kRows * 4;
-}
-
-template <int B, bool HZ, bool SINGLE>
-static int launch_x_group(int group, const KernelArgs<SINGLE>& a, int n_wg, int max_seg_tiles, hipStream_t st) {
-    const dim3 grid((unsigned)n_wg, (unsigned)a.n_gemv), block(kWaves * 64);
-    const unsigned lds = x_lds_bytes(max_seg_tiles);
-    switch (group) {
-        case 32: hipLaunchKernelGGL((mpgemv_x_kernel<B, 32, HZ, SINGLE>), grid, block, lds, st, a); break;
-        case 64: hipLaunchKernelGGL((mpgemv_x_kernel<B, 64, HZ, SINGLE>), grid, block, lds, st, a); break;
-        default: hipLaunchKernelGGL((mpgemv_x_kernel<B, 128, HZ, SINGLE>), grid, block, lds, st, a); break;
-    }
-    return launch_status();
-}
-
-template <bool SINGLE>
-static int launch_x_format(int bits, int has_zero, int group, const KernelArgs<SINGLE>& a, int n_wg, int max_seg_tiles,
-                           hipStream_t st) {
-    if (bits == 1) {
-        return has_zero ? launch_x_group<1, true, SINGLE>(group, a, n_wg, max_seg_tiles, st)
-                        : launch_x_group<1, false, SINGLE>(group, a, n_wg, max_seg_tiles, st);
-    }
-    if (bits == 2) return launch_x_group<2, true, SINGLE>(group, a, n_wg, max_seg_tiles, st);
-    return launch_x_group<4, true, SINGLE>(group, a, n_wg, max_seg_tiles, st);
-}
-
-int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y, void* workspace, hipStream_t st) {
-    KernelArgs<true> a;
-    fill_desc_x(a.single, L, packed, x, y, workspace);
-    a.n_gemv = 1;
-    const GemvPlan p = plan_gemv_x(L);
-    return launch_x_format<true>(L.bits, L.has_zero, L.group, a, p.n_workgroups, p.seg_tiles, st);
-}
-
-int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
-                          int max_seg_tiles, hipStream_t st) {
-    KernelArgs<false> a;
-    a.descs = descs_dev;
-    a.n_gemv = n_gemv;
-    return launch_x_format<false>(bits, has_zero, group, a, max_workgroups, max_seg_tiles, st);
-}
-
-// copies up to 16 descriptors per launch from the kernel arguments into the device table
+// Copies up to 16 descriptors per launch from the kernel arguments into the device table.  A GEMV whose blob
+// carries a header for another shape or layout gets an empty descriptor (no workgroup of the lookup launch
+// then touches it) and the mismatch is recorded in the library's status word.
 struct DescChunk {
     GemvDesc d[16];
 };
-__global__ void write_descs_kernel(DescChunk c, int count, GemvDesc* __restrict__ out) {
-    if ((int)threadIdx.x < count) out[threadIdx.x] = c.d[threadIdx.x];
+__global__ void write_descs_kernel(DescChunk c, int count, int bits, int group, int has_zero, GemvDesc* __restrict__ out,
+                                   int* status) {
+    if ((int)threadIdx.x >= count) return;
+    GemvDesc d = c.d[threadIdx.x];
+    if (!header_matches(d.tiles, d.M, d.K, bits, group, has_zero)) {
+        d.n_row_blocks = 0;
+        report_header_mismatch(status);
+    }
+    out[threadIdx.x] = d;
 }
 
-int launch_write_descs(const GemvDesc* host, int count, GemvDesc* dev, hipStream_t st) {
+int launch_write_descs(const GemvDesc* host, int count, int bits, int group, int has_zero, GemvDesc* dev, hipStream_t st) {
+    int* status = device_status_word();
+    if (!status) return TMAN_ERR_LAUNCH;
     for (int i = 0; i < count; i += 16) {
         DescChunk c;
         int n = count - i < 16 ? count - i : 16;
         for (int j = 0; j < 16; ++j) c.d[j] = host[i + (j < n ? j : 0)];
-        hipLaunchKernelGGL(write_descs_kernel, dim3(1), dim3(64), 0, st, c, n, dev + i);
+        hipLaunchKernelGGL(write_descs_kernel, dim3(1), dim3(64), 0, st, c, n, bits, group, has_zero, dev + i, status);
     }
     return launch_status();
 }
