@@ -169,19 +169,6 @@ int tman_mpgemv_x_batch_prepare(int32_t count, const tman_shape_t *shapes, const
 int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t *shapes, const void *desc, void *stream);
 
 /*
- * How a one-token batch is cut into work for the resident workgroups (host only, informational; the same
- * cut tman_mpgemv_x_batch_prepare makes with max_slots = 3 x the compute units of the device).  The tile
- * blocks of the batch (GEMV after GEMV, row block after row block, K tile after K tile; tile block = 64 rows
- * x 128 columns) form one sequence that is cut into at most `max_slots` slots of nearly equal length, row
- * blocks of at most 40 tiles staying whole where the slot length allows.  `slots` receives six numbers per
- * slot: GEMV and linear tile index where the slot starts, its tile count, the index of its first interval
- * among the intervals of that row block, and the number of intervals of the row blocks of its first and of
- * its last interval (an interval = what a slot holds of one row block).  Returns the number of slots, 0 on
- * invalid arguments (max_slots in [1, 4096]).
- */
-int32_t tman_mpgemv_x_plan(int32_t count, const tman_shape_t *shapes, int32_t max_slots, int32_t *slots);
-
-/*
  * Packed blobs carry a 128-byte header (shape, tile geometry, layout version).
  * tman_check_packed compares it with `shape` on the host: it copies the header back on `stream` and WAITS for
  * the stream (the one blocking call of the library; meant for load time).  TMAN_ERR_HEADER on disagreement.

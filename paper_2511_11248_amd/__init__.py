@@ -20,7 +20,6 @@ from .api import (  # noqa: F401
     tman_noalloc_init,
     tman_check_packed,
     tman_device_status,
-    tman_mpgemv_x_plan,
     tman_mpgemv_noalloc,
     tman_mpgemm_tile_rows,
     tman_mpgemv_batch_desc_bytes,

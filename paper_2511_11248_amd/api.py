@@ -94,8 +94,6 @@ def _load():
         L.tman_check_packed.argtypes = [sp, vp, vp]
         L.tman_device_status.restype = C.c_int
         L.tman_device_status.argtypes = [vp]
-        L.tman_mpgemv_x_plan.restype = C.c_int32
-        L.tman_mpgemv_x_plan.argtypes = [C.c_int32, sp, C.c_int32, C.POINTER(C.c_int32)]
         L.tman_noalloc_init.restype = C.c_int
         L.tman_noalloc_init.argtypes = []
         L.tman_mpgemv_noalloc.restype = C.c_int
@@ -194,15 +192,6 @@ def tman_check_packed(shape: Shape, packed, stream=None) -> int:
 def tman_device_status(stream=None) -> int:
     """Returns and clears the device status word (0, or -8 when a kernel met a blob with a foreign header)."""
     return int(_load().tman_device_status(_stream(stream)))
-
-
-def tman_mpgemv_x_plan(shapes, max_slots: int):
-    """The cut of a one-token batch into slots: list of (gemv, first, count, pidx0, nparts_first, nparts_last)."""
-    n = len(shapes)
-    cs = (_CShape * n)(*[s.c() for s in shapes])
-    buf = (C.c_int32 * (6 * max_slots))()
-    k = int(_load().tman_mpgemv_x_plan(n, cs, max_slots, buf))
-    return [tuple(buf[6 * i:6 * i + 6]) for i in range(k)]
 
 
 def tman_noalloc_init() -> None:

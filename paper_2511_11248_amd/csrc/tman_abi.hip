@@ -1,7 +1,6 @@
 // C ABI of libtman: argument validation, size queries and dispatch to the kernel launchers.
 // Everything here runs on the host and validates before anything is enqueued.
 #include <mutex>
-#include <vector>
 
 #include "tman_internal.h"
 
@@ -55,9 +54,9 @@ size_t tman_mpgemv_workspace_bytes(const tman_shape_t* shape, int32_t N) {
     const Layout L = make_layout(shape);
     GemvPlan p = plan_gemv(L, N);
     size_t need = p.ticket_bytes + p.partial_bytes;
-    if (N == 1) {  // also serves tman_mpgemv_x, which cuts the work differently
-        const size_t nx = x_workspace_bytes(L);
-        if (nx > need) need = nx;
+    if (N == 1) {  // also serves tman_mpgemv_x, which cuts K into shorter segments
+        GemvPlan px = plan_gemv_x(L);
+        if (px.ticket_bytes + px.partial_bytes > need) need = px.ticket_bytes + px.partial_bytes;
     }
     return need;
 }
@@ -126,8 +125,7 @@ int tman_mpgemv(const tman_shape_t* shape, const void* packed, const void* lut, 
 
 size_t tman_mpgemv_batch_desc_bytes(int32_t count) {
     if (count < 1 || count > TMAN_MAX_BATCH) return 0;
-    const size_t a = (size_t)count * sizeof(GemvDesc), b = x_desc_bytes(count);  // either kind of batch
-    return a > b ? a : b;
+    return (size_t)count * sizeof(GemvDesc);
 }
 
 static int check_batch(int32_t count, const tman_shape_t* shapes, int32_t N) {
@@ -203,21 +201,17 @@ int tman_mpgemv_x_batch_prepare(int32_t count, const tman_shape_t* shapes, const
     if (rc != TMAN_OK) return rc;
     if (!packed || !x || !y || !workspace || !workspace_bytes || !desc) return TMAN_ERR_NULL;
     if (!aligned16(desc)) return TMAN_ERR_ALIGN;
-    std::vector<XDesc> host((size_t)count);
+    GemvDesc host[TMAN_MAX_BATCH];
     for (int i = 0; i < count; ++i) {
         if (!packed[i] || !x[i] || !y[i] || !workspace[i]) return TMAN_ERR_NULL;
         if (!aligned16(packed[i]) || !aligned16(x[i]) || !aligned16(workspace[i])) return TMAN_ERR_ALIGN;
         if (workspace_bytes[i] < tman_mpgemv_workspace_bytes(&shapes[i], 1)) return TMAN_ERR_WORKSPACE;
         for (int j = 0; j < i; ++j)
             if (workspace[j] == workspace[i]) return TMAN_ERR_WORKSPACE;  // every GEMV needs its own
-        fill_xdesc(host[i], make_layout(&shapes[i]), packed[i], x[i], y[i], workspace[i]);
+        fill_desc_x(host[i], make_layout(&shapes[i]), packed[i], x[i], y[i], workspace[i]);
     }
-    // the cut of the launch's tile blocks into one slot per resident workgroup
-    const int S = x_slots_of_device();
-    std::vector<XSlot> slots((size_t)S);
-    const int n_slots = x_schedule(host.data(), count, S, slots.data());
-    if (n_slots < 1) return TMAN_ERR_SHAPE;
-    return launch_mpgemv_x_prepare(host.data(), count, slots.data(), n_slots, desc, (hipStream_t)stream);
+    return launch_write_descs(host, count, shapes[0].bits, shapes[0].group, (shapes[0].flags & TMAN_FLAG_HAS_ZERO) ? 1 : 0,
+                              static_cast<GemvDesc*>(desc), (hipStream_t)stream);
 }
 
 int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t* shapes, const void* desc, void* stream) {
@@ -225,22 +219,14 @@ int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t* shapes, const voi
     if (rc != TMAN_OK) return rc;
     if (!desc) return TMAN_ERR_NULL;
     if (!aligned16(desc)) return TMAN_ERR_ALIGN;
-    return launch_mpgemv_x_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO, desc, count,
-                                 (hipStream_t)stream);
-}
-
-int32_t tman_mpgemv_x_plan(int32_t count, const tman_shape_t* shapes, int32_t max_slots, int32_t* slots) {
-    if (check_batch(count, shapes, 1) != TMAN_OK || !slots || max_slots < 1 || max_slots > kXMaxSlots) return 0;
-    std::vector<XDesc> host((size_t)count);
-    for (int i = 0; i < count; ++i) fill_xdesc(host[i], make_layout(&shapes[i]), nullptr, nullptr, nullptr, nullptr);
-    std::vector<XSlot> cut((size_t)max_slots);
-    const int n = x_schedule(host.data(), count, max_slots, cut.data());
-    for (int i = 0; i < n; ++i) {
-        const XSlot& c = cut[(size_t)i];
-        const int32_t row[6] = {c.gemv, c.first, c.count, c.pidx0, c.nparts_first, c.nparts_last};
-        for (int j = 0; j < 6; ++j) slots[i * 6 + j] = row[j];
+    int max_wg = 0, max_seg_tiles = 0;  // grid = (workgroups of the largest GEMV) x count; LDS for the longest segment
+    for (int i = 0; i < count; ++i) {
+        const GemvPlan p = plan_gemv_x(make_layout(&shapes[i]));
+        if (p.n_workgroups > max_wg) max_wg = p.n_workgroups;
+        if (p.seg_tiles > max_seg_tiles) max_seg_tiles = p.seg_tiles;
     }
-    return n;
+    return launch_mpgemv_x_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO,
+                                 static_cast<const GemvDesc*>(desc), count, max_wg, max_seg_tiles, (hipStream_t)stream);
 }
 
 int32_t tman_mpgemm_tile_rows(const tman_shape_t* shape, int32_t N) {

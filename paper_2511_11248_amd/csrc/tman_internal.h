@@ -61,11 +61,14 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? TMAN_OK : TMAN_ERR_LAUNCH; }
 
-// Does the header in front of the tile blocks describe this shape?  (Scalar loads; 14 words are defined.)
+// Does the header in front of the tile blocks describe this shape?  The 14 defined words are fetched with one
+// 64-byte load and compared without branches, so the check costs one memory round trip.
+typedef int32_t header_words_t __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ bool header_matches(const uint8_t* tiles, int M, int K, int bits, int group, int has_zero) {
-    const int32_t* h = reinterpret_cast<const int32_t*>(tiles - kHeaderBytes);
-    return h[0] == 0x4e414d54 && h[1] == 0x00314b50 && h[2] == M && h[3] == K && h[4] == bits && h[5] == group &&
-           h[6] == has_zero && h[7] == kRows && h[8] == kKTile && h[12] == kHeaderBytes && h[13] == kLayoutVersion;
+    const header_words_t h = *reinterpret_cast<const header_words_t*>(tiles - kHeaderBytes);
+    const int diff = (h[0] ^ 0x4e414d54) | (h[1] ^ 0x00314b50) | (h[2] ^ M) | (h[3] ^ K) | (h[4] ^ bits) | (h[5] ^ group) |
+                     (h[6] ^ has_zero) | (h[7] ^ kRows) | (h[8] ^ kKTile) | (h[12] ^ kHeaderBytes) | (h[13] ^ kLayoutVersion);
+    return diff == 0;
 }
 
 // What a kernel does when it meets a blob whose header disagrees with the shape it was launched for: one thread
@@ -101,43 +104,14 @@ struct GemvPlan {
     size_t partial_bytes;
 };
 GemvPlan plan_gemv(const Layout& L, int N);
-// ---- one-token decode with the tables built in the lookup kernel (tman_mpgemv_x*) ----
-//
-// The tile blocks of a launch (all its GEMVs, row block after row block, K tile after K tile) form one linear
-// sequence that is cut into `slots` of nearly equal length, one per workgroup, as many workgroups as stay
-// resident at once (kXSlotsPerCu per compute unit).  What a slot holds of one row block is an `interval`; a row
-// block that several slots share is summed through the workspace.
-constexpr int kXPieceTiles = 40;    // tile blocks whose tables a workgroup holds in LDS at a time (40 KB)
-constexpr int kXSlotsPerCu = 3;     // workgroups per compute unit (their LDS admits exactly this many)
-constexpr int kXMaxSlots = 4096;    // room in a descriptor buffer
-constexpr int kXMinSlotTiles = 8;   // a slot that does not end a launch is never shorter: bounds the intervals of a row block
-
-struct XDesc {
-    const uint8_t* tiles;  // first tile block (past the header)
-    const uint8_t* x;      // activations, fp16 [K]
-    void* y;               // fp16 [M]
-    int32_t* tickets;      // [n_row_blocks]: tile blocks of the row block summed so far; zero between launches
-    float* partial;        // [n_row_blocks][parts_per_row][64]
-    int M, K, n_row_blocks, n_ktiles;
-    int parts_per_row;
-    int valid;             // the blob's header agrees with the shape (decided on the device)
-    int bits, group, has_zero, pad;
-};
-
-struct XSlot {
-    int gemv, first, count;  // `count` tile blocks from linear tile `first` of GEMV `gemv` on, continuing into the next GEMVs
-    int pidx0;               // index of the slot's first interval among the intervals of its row block
-    int nparts_first;        // intervals of the row block of the slot's first interval
-    int nparts_last;         // the same for its last interval (which, if not also the first, has index 0)
-    int pad0, pad1;
-};
-
-inline int x_parts_per_row(int n_ktiles) { return n_ktiles / kXMinSlotTiles + 2; }
-size_t x_workspace_bytes(const Layout& L);
-void fill_xdesc(XDesc& d, const Layout& L, const void* packed, const void* x, void* y, void* workspace);
-// Cuts the launch into at most `max_slots` slots; returns their number (0 if the launch does not fit).
-int x_schedule(const XDesc* descs, int count, int max_slots, XSlot* slots);
-int x_slots_of_device();  // kXSlotsPerCu * compute units of the current device
+GemvPlan plan_segments(const Layout& L, int np, int max_seg);
+// Plan of the one-token kernel that builds its tables itself: at most 32 tiles per segment (32 KB of tables
+// in LDS), 24 when K has to be cut anyway.
+constexpr int kGemvXSegmentTiles = 32;
+constexpr int kGemvXLongSegmentTiles = 24;
+GemvPlan plan_gemv_x(const Layout& L);
+void fill_desc_plan(GemvDesc& d, const Layout& L, const GemvPlan& p, const void* packed, const void* lut, int N, void* y,
+                    void* workspace, int wg_begin);
 void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
                int wg_begin);
 
@@ -153,11 +127,10 @@ int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, v
 int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,
                         int max_workgroups, hipStream_t st);
 // one token, tables built inside the lookup kernel from the activations x (fp16 [K])
+void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x, void* y, void* workspace);
 int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y, void* workspace, hipStream_t st);
-int launch_mpgemv_x_prepare(const XDesc* host_descs, int count, const XSlot* host_slots, int n_slots, void* desc_dev,
-                            hipStream_t st);
-int launch_mpgemv_x_batch(int bits, int group, int has_zero, const void* desc_dev, int n_gemv, hipStream_t st);
-size_t x_desc_bytes(int count);
+int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
+                          int max_seg_tiles, hipStream_t st);
 int* device_status_word();  // device address of the library's status word on the current device (nullptr on failure)
 int launch_write_descs(const GemvDesc* host, int count, int bits, int group, int has_zero, GemvDesc* dev, hipStream_t st);
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);

@@ -242,12 +242,12 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
     // that share the weights of one row tile get ids that are 8 apart, i.e. the same XCD and L2.
     const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
     const int mt = (slot / a.n_tiles) * kXcds + xcd, nt = slot % a.n_tiles;
-    if (mt >= a.m_tiles) return;
-    // a blob packed for another shape or layout: leave y alone and say so
-    if (!header_matches(a.tiles, a.M, a.K, B, GQ, HZ ? 1 : 0)) {
-        if (blockIdx.x == 0 && threadIdx.x == 0) report_header_mismatch(a.status);
-        return;
-    }
+    // A blob packed for another shape or layout: say so and leave y alone.  (The check is folded into the one
+    // exit below: a second exit after this load makes the compiler keep the dequantization state in scratch
+    // memory.)
+    const bool header_ok = header_matches(a.tiles, a.M, a.K, B, GQ, HZ ? 1 : 0);
+    if (!header_ok && blockIdx.x == 0 && threadIdx.x == 0) report_header_mismatch(a.status);
+    if (mt >= (header_ok ? a.m_tiles : 0)) return;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;

@@ -35,7 +35,7 @@ namespace tman {
 // ---------------------------------------------------------------------------------------------
 // host-side planning
 
-static GemvPlan plan_segments(const Layout& L, int np, int max_seg) {
+GemvPlan plan_segments(const Layout& L, int np, int max_seg) {
     GemvPlan p;
     p.np = np;
     p.n_seg = (L.n_ktiles + max_seg - 1) / max_seg;
@@ -53,7 +53,7 @@ GemvPlan plan_gemv(const Layout& L, int N) {
     return plan_segments(L, np, np >= 4 ? kGemvManyTokensSegmentTiles : kGemvSegmentTiles);
 }
 
-static void fill_desc_plan(GemvDesc& d, const Layout& L, const GemvPlan& p, const void* packed, const void* lut, int N,
+void fill_desc_plan(GemvDesc& d, const Layout& L, const GemvPlan& p, const void* packed, const void* lut, int N,
                            void* y, void* workspace, int wg_begin) {
     d.tiles = static_cast<const uint8_t*>(packed) + kHeaderBytes;
     d.lut_t = static_cast<const uint8_t*>(lut);
@@ -78,21 +78,6 @@ void fill_desc(GemvDesc& d, const Layout& L, const void* packed, const void* lut
 
 // ---------------------------------------------------------------------------------------------
 // device side
-
-// kernel arguments: the descriptor itself for a single GEMV, the device table for a batch
-template <bool SINGLE>
-struct KernelArgs;
-template <>
-struct KernelArgs<true> {
-    GemvDesc single;
-    int n_gemv;   // 1
-    int* status;  // the library's status word
-};
-template <>
-struct KernelArgs<false> {
-    const GemvDesc* descs;
-    int n_gemv;
-};
 
 // Requests tile kt: its weights, its slice of the lookup tables and its group sums (same rule for `live`).
 template <int B, int NP, int GQ, bool HZ>
@@ -256,69 +241,6 @@ __device__ __forceinline__ void consume_tile(const Stage<B, NP, GemvCfg<B, NP, G
         asm volatile("" ::: "memory");
         __builtin_amdgcn_sched_barrier(0);
     }
-}
-
-template <bool SINGLE>
-__device__ __forceinline__ const GemvDesc& desc_of(const KernelArgs<SINGLE>& a, int g) {
-    if constexpr (SINGLE) {
-        return a.single;
-    } else {
-        return a.descs[g];
-    }
-}
-
-// Output of one row block by its first wave: y holds the sums of the workgroup's K segment for the lane's
-// row.  With one segment they are the result; otherwise the segments meet through memory (see above).
-template <int NP>
-__device__ __forceinline__ void finish_rows(const GemvDesc& d, int rb, int seg, int n_seg, int lane, float (&y)[NP]) {
-    const int m = rb * kRows + lane;
-    const int M = d.M, N = d.N;
-    _Float16* out = static_cast<_Float16*>(d.y);
-    if (n_seg == 1) {
-        if (m < M) {
-#pragma unroll
-            for (int n = 0; n < NP; ++n)
-                if (n < N) out[(size_t)n * M + m] = (_Float16)y[n];
-        }
-        return;
-    }
-
-    // K longer than one segment: publish this segment's partial sums and take a ticket
-    float* base_p = d.partial + (size_t)rb * n_seg * NP * kRows;
-    float* mine = base_p + (size_t)seg * NP * kRows;
-#pragma unroll
-    for (int n = 0; n < NP; ++n)
-        __hip_atomic_store(mine + n * kRows + lane, y[n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the partials have reached device-coherent memory
-    int32_t* ticket = d.tickets + rb;
-    int prev = 0;
-    if (lane == 0) prev = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    prev = __builtin_amdgcn_readfirstlane(prev);
-    if (prev != n_seg - 1) return;
-    // last ticket: every segment of this row block has been published; add them in segment order
-    float acc[NP];
-#pragma unroll
-    for (int n = 0; n < NP; ++n) acc[n] = 0.f;
-    for (int p0 = 0; p0 < n_seg; p0 += 4) {
-        float v[4][NP];
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int n = 0; n < NP; ++n)
-                v[q][n] = (p0 + q < n_seg) ? __hip_atomic_load(base_p + ((size_t)(p0 + q) * NP + n) * kRows + lane,
-                                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                           : 0.f;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-#pragma unroll
-            for (int n = 0; n < NP; ++n) acc[n] += v[q][n];
-    }
-    if (m < M) {
-#pragma unroll
-        for (int n = 0; n < NP; ++n)
-            if (n < N) out[(size_t)n * M + m] = (_Float16)acc[n];
-    }
-    if (lane == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int B, int NP, int GQ, bool HZ, bool SINGLE>
