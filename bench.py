@@ -124,9 +124,23 @@ def decode_job(torch, tman, synth, dev, w, N, n_inst):
             x_descs.append(d)
         torch.cuda.synchronize()
         x_calls = [tman.bound_mpgemv_x_batch_run(shapes, x_descs[inst]) for inst in range(n_inst)]
+    # a few tokens: the same product on the matrix cores (tman_mpgemm's small-batch kernel), one launch per layer set
+    mm_calls, mm_keep = None, []
+    if N > 1:
+        mm_ws = []
+        for s in shapes:
+            need = tman.tman_mpgemm_workspace_bytes(s, N)
+            mm_ws.append(torch.zeros(need, dtype=torch.uint8, device=dev) if need else None)
+        for inst in range(n_inst):
+            d = torch.empty(tman.tman_mpgemv_batch_desc_bytes(len(shapes)), dtype=torch.uint8, device=dev)
+            tman.tman_mpgemm_batch_prepare(shapes, blobs[inst], [xs[inst][a] for a in act_of_layer], N, ys, mm_ws, d)
+            mm_keep.append(d)
+        torch.cuda.synchronize()
+        mm_calls = [tman.bound_mpgemm_batch_run(shapes, N, mm_keep[inst]) for inst in range(n_inst)]
+        mm_keep.append(mm_ws)
     return {"shapes": shapes, "acts": acts, "weight_bytes_per_step": weight_bytes_per_step, "ys": ys,
-            "lut_calls": lut_calls, "gemv_calls": gemv_calls, "x_calls": x_calls, "stream": stream,
-            "keep": (blobs, xs, luts, wss, descs, x_descs)}  # the launches hold raw pointers into these
+            "lut_calls": lut_calls, "gemv_calls": gemv_calls, "x_calls": x_calls, "mm_calls": mm_calls, "stream": stream,
+            "keep": (blobs, xs, luts, wss, descs, x_descs, mm_keep)}  # the launches hold raw pointers into these
 
 
 def timed_steps(torch, step, warm, steps):
@@ -141,8 +155,10 @@ def timed_steps(torch, step, warm, steps):
     return (time.perf_counter() - t0) / steps
 
 
-def decode_step_fn(job, n_inst):
+def decode_step_fn(job, n_inst, matrix_cores=False):
     stream = job["stream"]
+    if matrix_cores:  # a few tokens, dequantized in registers and multiplied on the matrix cores: one launch
+        return lambda i: job["mm_calls"][i % n_inst](stream)
     if job["x_calls"] is not None:  # one token: one launch
         return lambda i: job["x_calls"][i % n_inst](stream)
 
@@ -153,10 +169,12 @@ def decode_step_fn(job, n_inst):
     return two
 
 
-def decode_error(torch, synth, oracle, w, job, N, inst=0):
+def decode_error(torch, synth, oracle, w, job, N, inst=0, matrix_cores=False):
     """Largest row-normalised error of the outputs of the step on copy `inst` against the fp64 oracle, and the
     oracle's time."""
-    decode_step_fn(job, max(inst + 1, 1))(inst)
+    for y in job["ys"]:
+        y.fill_(float("nan"))
+    decode_step_fn(job, max(inst + 1, 1), matrix_cores)(inst)
     torch.cuda.synchronize()
     err, cpu_t, used = 0.0, 0.0, 1
     for li in range(len(job["shapes"])):
@@ -207,6 +225,13 @@ def other_configs(args, torch, tman, synth, oracle, dev):
             kind = "one launch per layer set" if job["x_calls"] is not None else "table launch + lookup launch per layer set"
             add(f"{name} N={N}, {w.instances} rotating copies, {kind}" + (" (cache-resident: correctness only)" if w.instances == 1 else ""),
                 sec, gbs, "GB/s", HBM_PEAK_GBS, err, "all outputs of copy 0")
+            if N > 1:  # the same tokens through the matrix-core kernel
+                step = decode_step_fn(job, w.instances, matrix_cores=True)
+                sec = timed_steps(torch, step, 100, 300)
+                err, _, _ = decode_error(torch, synth, oracle, w, job, N, matrix_cores=True)
+                add(f"{name} N={N}, {w.instances} rotating copies, one tman_mpgemm_batch launch per layer set "
+                    f"(dequantization in registers + MFMA)", sec, job["weight_bytes_per_step"] / sec / 1e9, "GB/s",
+                    HBM_PEAK_GBS, err, "all outputs of copy 0")
             if w.config == 4:  # the whole 32-layer weight stream as one launch of 160 GEMVs
                 big = whole_model_launch(torch, tman, dev, w, job)
                 stream = job["stream"]

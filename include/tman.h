@@ -183,20 +183,38 @@ int tman_check_packed(const tman_shape_t *shape, const void *packed, void *strea
 int tman_device_status(void *stream);
 
 /*
- * Prefill mpGEMM (Sec. 4.1 "Fused LUT-based dequantization", Sec. 4.2): bit-planes are repacked to
+ * mpGEMM on the matrix cores (Sec. 4.1 "Fused LUT-based dequantization", Sec. 4.2): bit-planes are repacked to
  * codes (level 1), each code is looked up in its quantization block's table
  * D[c] = fp16((c - zero) * scale) (level 2; sign form fp16((2c - 1) * scale)), and the fp16 weights
  * feed the matrix cores with fp32 accumulation.
  *   x : fp16 [N][K], any N >= 1;   y : fp16 [N][M]
- *   workspace : tman_mpgemm_workspace_bytes(shape, N) bytes.  The query returns 0 for every shape today (the
- *               kernel needs no scratch memory); the arguments are kept so that a later split of K across
- *               workgroups does not change the signature.  NULL / 0 is accepted.
+ * Two kernels share the call.  N > TMAN_MAX_SMALL_TOKENS runs the tiled prefill kernel (256 tokens per
+ * workgroup, bound by the matrix cores; it needs no workspace).  1 <= N <= TMAN_MAX_SMALL_TOKENS runs a kernel
+ * organised like the decoding kernels (bound by the weight stream: every wave dequantizes the tile blocks it
+ * streams and multiplies them with all tokens at once), which cuts a long K into segments that meet in the
+ * workspace, under the rules of tman_mpgemv: tman_mpgemm_workspace_bytes(shape, N) bytes (0 when K is one
+ * segment, then NULL is accepted), 16-byte aligned, zero-filled once before first use, left ready by every
+ * call, not shared by calls that may overlap.  Deterministic.
  */
+#define TMAN_MAX_SMALL_TOKENS 32
 int tman_mpgemm(const tman_shape_t *shape, const void *packed, const void *x, int32_t N, void *y, void *workspace,
                 size_t workspace_bytes, void *stream);
 
 /*
- * Rows of W (output features) one workgroup of tman_mpgemm covers for this shape and N: 64, 128, 192 or 256,
+ * Several small-batch mpGEMMs (the same N <= TMAN_MAX_SMALL_TOKENS, the same bits / group / flags) in one
+ * launch, e.g. the linear layers of a decode step with a few tokens in flight (Sec. 5: layers fed by one
+ * activation share it; here entries of `x` may repeat).  Arguments as for tman_mpgemv_batch_prepare / _run with
+ * the activations `x` (fp16 [N][K] each) in place of the table buffers; workspace[i] may be NULL where
+ * tman_mpgemm_workspace_bytes(&shapes[i], N) is 0; the descriptor table takes
+ * tman_mpgemv_batch_desc_bytes(count) bytes.
+ */
+int tman_mpgemm_batch_prepare(int32_t count, const tman_shape_t *shapes, const void *const *packed,
+                              const void *const *x, int32_t N, void *const *y, void *const *workspace,
+                              const size_t *workspace_bytes, void *desc, void *stream);
+int tman_mpgemm_batch_run(int32_t count, const tman_shape_t *shapes, int32_t N, const void *desc, void *stream);
+
+/*
+ * Rows of W (output features) one workgroup of tman_mpgemm's tiled kernel covers for this shape and N: 64, 128, 192 or 256,
  * chosen so that the workgroups fill the compute units of the current device best (256 units are
  * assumed when no device is present).  Informational; 0 for an invalid shape or N < 1.
  */

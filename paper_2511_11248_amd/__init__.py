@@ -22,6 +22,9 @@ from .api import (  # noqa: F401
     tman_device_status,
     tman_mpgemv_noalloc,
     tman_mpgemm_tile_rows,
+    tman_mpgemm_batch_prepare,
+    tman_mpgemm_batch_run,
+    bound_mpgemm_batch_run,
     tman_mpgemv_batch_desc_bytes,
     tman_mpgemv_batch_prepare,
     tman_mpgemv_batch_run,

@@ -88,6 +88,10 @@ def _load():
         L.tman_mpgemv_x_batch_run.argtypes = [C.c_int32, sp, vp, vp]
         L.tman_mpgemm.restype = C.c_int
         L.tman_mpgemm.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.tman_mpgemm_batch_prepare.restype = C.c_int
+        L.tman_mpgemm_batch_prepare.argtypes = [C.c_int32, sp, vp, vp, C.c_int32, vp, vp, vp, vp, vp]
+        L.tman_mpgemm_batch_run.restype = C.c_int
+        L.tman_mpgemm_batch_run.argtypes = [C.c_int32, sp, C.c_int32, vp, vp]
         L.tman_mpgemm_tile_rows.restype = C.c_int32
         L.tman_mpgemm_tile_rows.argtypes = [sp, C.c_int32]
         L.tman_check_packed.restype = C.c_int
@@ -209,6 +213,35 @@ def tman_mpgemm(shape: Shape, packed, x, N: int, y, workspace=None, stream=None)
     wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
     _check(_load().tman_mpgemm(C.byref(shape.c()), _ptr(packed), _ptr(x), N, _ptr(y), _ptr(workspace), wb,
                                _stream(stream)), "tman_mpgemm")
+
+
+def tman_mpgemm_batch_prepare(shapes, packed, xs, N: int, y, workspace, desc, stream=None) -> None:
+    """Descriptor table for a batch of small-batch mpGEMMs (N <= 32); workspace entries may be None where the
+    size query gives 0."""
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    vp = C.c_void_p * n
+    wb = (C.c_size_t * n)(*[0 if t is None else _nbytes(t) for t in workspace])
+    _check(_load().tman_mpgemm_batch_prepare(n, cs, vp(*[_ptr(t) for t in packed]), vp(*[_ptr(t) for t in xs]), N,
+                                             vp(*[_ptr(t) for t in y]), vp(*[_ptr(t) for t in workspace]), wb,
+                                             _ptr(desc), _stream(stream)), "tman_mpgemm_batch_prepare")
+
+
+def tman_mpgemm_batch_run(shapes, N: int, desc, stream=None) -> None:
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    _check(_load().tman_mpgemm_batch_run(n, cs, N, _ptr(desc), _stream(stream)), "tman_mpgemm_batch_run")
+
+
+def bound_mpgemm_batch_run(shapes, N: int, desc):
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    fn, args = _load().tman_mpgemm_batch_run, (n, cs, N, _ptr(desc))
+
+    def call(stream_handle):
+        _check(fn(*args, stream_handle), "tman_mpgemm_batch_run")
+
+    return call
 
 
 def tman_mpgemv_batch_desc_bytes(count: int) -> int:

@@ -62,9 +62,10 @@ size_t tman_mpgemv_workspace_bytes(const tman_shape_t* shape, int32_t N) {
 }
 
 size_t tman_mpgemm_workspace_bytes(const tman_shape_t* shape, int32_t N) {
-    (void)shape;
-    (void)N;
-    return 0;
+    if (check_shape(shape) != TMAN_OK || N < 1) return 0;
+    if (N > TMAN_MAX_SMALL_TOKENS) return 0;  // the tiled prefill kernel needs no scratch memory
+    const GemvPlan p = plan_small(make_layout(shape));  // a long K is cut into segments that meet in the workspace
+    return p.n_seg > 1 ? p.ticket_bytes + p.partial_bytes : 0;
 }
 
 int tman_pack_weights(const tman_shape_t* shape, const uint8_t* codes, const void* scales, const void* zeros,
@@ -243,7 +244,54 @@ int tman_mpgemm(const tman_shape_t* shape, const void* packed, const void* x, in
     if (!aligned16(packed) || !aligned16(x)) return TMAN_ERR_ALIGN;
     size_t need = tman_mpgemm_workspace_bytes(shape, N);
     if (need && (!workspace || workspace_bytes < need)) return TMAN_ERR_WORKSPACE;
-    return launch_mpgemm(make_layout(shape), packed, x, N, y, workspace, (hipStream_t)stream);
+    if (need && !aligned16(workspace)) return TMAN_ERR_ALIGN;
+    const Layout L = make_layout(shape);
+    if (N <= TMAN_MAX_SMALL_TOKENS) {
+        if ((long long)N * L.K * 2 > 0xFFFFFFF0LL) return TMAN_ERR_SHAPE;  // the activations are one buffer resource
+        return launch_mpgemm_small(L, packed, x, N, y, need ? workspace : nullptr, (hipStream_t)stream);
+    }
+    return launch_mpgemm(L, packed, x, N, y, workspace, (hipStream_t)stream);
+}
+
+int tman_mpgemm_batch_prepare(int32_t count, const tman_shape_t* shapes, const void* const* packed,
+                              const void* const* x, int32_t N, void* const* y, void* const* workspace,
+                              const size_t* workspace_bytes, void* desc, void* stream) {
+    int rc = check_batch(count, shapes, 1);
+    if (rc != TMAN_OK) return rc;
+    if (N < 1 || N > TMAN_MAX_SMALL_TOKENS) return TMAN_ERR_SHAPE;
+    if (!packed || !x || !y || !workspace || !workspace_bytes || !desc) return TMAN_ERR_NULL;
+    if (!aligned16(desc)) return TMAN_ERR_ALIGN;
+    GemvDesc host[TMAN_MAX_BATCH];
+    for (int i = 0; i < count; ++i) {
+        if (!packed[i] || !x[i] || !y[i]) return TMAN_ERR_NULL;
+        if (!aligned16(packed[i]) || !aligned16(x[i])) return TMAN_ERR_ALIGN;
+        const size_t need = tman_mpgemm_workspace_bytes(&shapes[i], N);
+        if (need) {
+            if (!workspace[i] || workspace_bytes[i] < need) return TMAN_ERR_WORKSPACE;
+            if (!aligned16(workspace[i])) return TMAN_ERR_ALIGN;
+            for (int j = 0; j < i; ++j)
+                if (workspace[j] == workspace[i]) return TMAN_ERR_WORKSPACE;  // every GEMM needs its own
+        }
+        if ((long long)N * shapes[i].K * 2 > 0xFFFFFFF0LL) return TMAN_ERR_SHAPE;
+        fill_desc_small(host[i], make_layout(&shapes[i]), packed[i], x[i], N, y[i], need ? workspace[i] : nullptr);
+    }
+    return launch_write_descs(host, count, shapes[0].bits, shapes[0].group, (shapes[0].flags & TMAN_FLAG_HAS_ZERO) ? 1 : 0,
+                              static_cast<GemvDesc*>(desc), (hipStream_t)stream);
+}
+
+int tman_mpgemm_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, const void* desc, void* stream) {
+    int rc = check_batch(count, shapes, 1);
+    if (rc != TMAN_OK) return rc;
+    if (N < 1 || N > TMAN_MAX_SMALL_TOKENS) return TMAN_ERR_SHAPE;
+    if (!desc) return TMAN_ERR_NULL;
+    if (!aligned16(desc)) return TMAN_ERR_ALIGN;
+    int max_wg = 0;  // the launch grid is (workgroups of the largest GEMM) x count
+    for (int i = 0; i < count; ++i) {
+        const int n = plan_small(make_layout(&shapes[i])).n_workgroups;
+        if (n > max_wg) max_wg = n;
+    }
+    return launch_mpgemm_small_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO,
+                                     static_cast<const GemvDesc*>(desc), count, max_wg, (hipStream_t)stream);
 }
 
 int tman_check_packed(const tman_shape_t* shape, const void* packed, void* stream) {

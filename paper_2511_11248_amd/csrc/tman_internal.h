@@ -131,6 +131,12 @@ void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x
 int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y, void* workspace, hipStream_t st);
 int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
                           int max_seg_tiles, hipStream_t st);
+// a handful of tokens on the matrix cores, scheduled like the decoding kernels (tman_mpgemm with N <= 32, and its batch form)
+GemvPlan plan_small(const Layout& L);
+void fill_desc_small(GemvDesc& d, const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace);
+int launch_mpgemm_small(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);
+int launch_mpgemm_small_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
+                              hipStream_t st);
 int* device_status_word();  // device address of the library's status word on the current device (nullptr on failure)
 int launch_write_descs(const GemvDesc* host, int count, int bits, int group, int has_zero, GemvDesc* dev, hipStream_t st);
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);

@@ -77,6 +77,8 @@ def mpgemm(shape, blob, x):
     xd = x if torch.is_tensor(x) else to_dev(x)
     N = xd.shape[0]
     y = torch.full((N, shape.M), float("nan"), dtype=torch.float16, device=dev())
-    tman.tman_mpgemm(shape, blob, xd, N, y, None)
+    need = tman.tman_mpgemm_workspace_bytes(shape, N)
+    ws = torch.zeros(need, dtype=torch.uint8, device=dev()) if need else None
+    tman.tman_mpgemm(shape, blob, xd, N, y, ws)
     torch.cuda.synchronize()
     return y.cpu().numpy()
