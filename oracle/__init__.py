@@ -8,6 +8,9 @@ from .oracle import (  # noqa: F401
     lib,
     matmul,
     lut_matmul,
+    quantize_activations,
+    matmul_real_x,
+    lut_matmul_i16,
     table_dequant_matmul,
     build_tables,
     lut_indices,

@@ -52,6 +52,13 @@ def lib():
         L.tman_oracle_dequant_table.argtypes = [C.c_uint16, C.c_uint16, C.c_int, C.c_int, u16p]
         L.tman_oracle_table_dequant_matmul.restype = None
         L.tman_oracle_table_dequant_matmul.argtypes = [u8p, u16p, u16p, u16p] + [C.c_int] * 6 + [f64p]
+        i16p, i32p, i64p = C.POINTER(C.c_int16), C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+        L.tman_oracle_quantize_activations.restype = None
+        L.tman_oracle_quantize_activations.argtypes = [u16p, C.c_int, C.c_int, i16p, i32p]
+        L.tman_oracle_matmul_real_x.restype = None
+        L.tman_oracle_matmul_real_x.argtypes = [u8p, u16p, u16p, f64p] + [C.c_int] * 5 + [f64p]
+        L.tman_oracle_lut_matmul_i16.restype = C.c_int
+        L.tman_oracle_lut_matmul_i16.argtypes = [u8p, u16p, u16p, i16p, i32p] + [C.c_int] * 6 + [f64p, i64p]
         _lib = L
     return _lib
 
@@ -104,6 +111,45 @@ def table_dequant_matmul(q, scale, zero, x, bits: int, group: int):
     lib().tman_oracle_table_dequant_matmul(_p(q, C.c_uint8), _p(s, C.c_uint16), _p(z, C.c_uint16), _p(xb, C.c_uint16),
                                            N, M, K, bits, group, int(zero is None), _p(Y, C.c_double))
     return Y
+
+
+def quantize_activations(x):
+    """Integer activations of the A_INT16 reading: (xq int16 [N][K] with |xq| <= 8191, e int32 [N]) with
+    xq = RNE(x / 2^e), 2^e the smallest power of two that brings every activation of the token within 8191."""
+    x = np.ascontiguousarray(x, dtype=np.float16)
+    N, K = x.shape
+    xq = np.empty((N, K), dtype=np.int16)
+    e = np.empty(N, dtype=np.int32)
+    lib().tman_oracle_quantize_activations(_p(x.view(np.uint16), C.c_uint16), N, K, _p(xq, C.c_int16), _p(e, C.c_int32))
+    return xq, e
+
+
+def matmul_real_x(q, scale, zero, xd, bits: int, group: int):
+    """The definition for activations given as doubles [N][K] (e.g. dequantized integer activations)."""
+    xd = np.ascontiguousarray(xd, dtype=np.float64)
+    N, K = xd.shape
+    q, s, z, _, _, M, K2 = _prep(q, scale, zero, np.zeros((1, K), np.float16), bits, group)
+    assert K2 == K
+    Y = np.empty((N, M), dtype=np.float64)
+    lib().tman_oracle_matmul_real_x(_p(q, C.c_uint8), _p(s, C.c_uint16), _p(z, C.c_uint16), _p(xd, C.c_double), N, M, K,
+                                    group, int(zero is None), _p(Y, C.c_double))
+    return Y
+
+
+def lut_matmul_i16(q, scale, zero, xq, e, bits: int, group: int, return_block_sums: bool = False):
+    """Table-lookup form on integer activations: integer tables, integer sums inside a quantization block."""
+    xq = np.ascontiguousarray(xq, dtype=np.int16)
+    e = np.ascontiguousarray(e, dtype=np.int32)
+    N, K = xq.shape
+    q, s, z, _, _, M, K2 = _prep(q, scale, zero, np.zeros((1, K), np.float16), bits, group)
+    assert K2 == K and e.shape == (N,)
+    Y = np.empty((N, M), dtype=np.float64)
+    A = np.empty((N, M, K // group), dtype=np.int64) if return_block_sums else None
+    over = lib().tman_oracle_lut_matmul_i16(_p(q, C.c_uint8), _p(s, C.c_uint16), _p(z, C.c_uint16), _p(xq, C.c_int16),
+                                            _p(e, C.c_int32), N, M, K, bits, group, int(zero is None), _p(Y, C.c_double),
+                                            _p(A, C.c_int64))
+    assert over == 0, "a table entry does not fit 16 bits"
+    return (Y, A) if return_block_sums else Y
 
 
 def build_tables(x, g: int = 4) -> np.ndarray:

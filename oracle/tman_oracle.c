@@ -252,3 +252,113 @@ void tman_oracle_table_dequant_matmul(const uint8_t *q, const uint16_t *scale, c
     }
     free(wd);
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Integer activations and integer tables (Sec. 6.1 "A_INT16"; Sec. 4.3 two-level tiling: table entries are
+ * aggregated at low precision inside a quantization block, in floating point only across blocks; Sec. 5:
+ * 16-bit table entries).
+ *
+ * Reading used here (the paper gives no quantizer): every token n gets a power-of-two step 2^e[n], the
+ * smallest for which all |x[n][k]| / 2^e[n] <= 8191, and integer activations
+ *     xq[n][k] = round_to_nearest_even( x[n][k] / 2^e[n] ),   |xq| <= 8191
+ * so that the sum of any four of them fits a 16-bit table entry exactly.  Dividing an fp16 number by a power
+ * of two is exact, so the integer is the same in any precision.  With max|x| = m * 2^E (0.5 <= m < 1) the
+ * exponent is e = E - 13 (m <= 1 - 2^-11 for an fp16 number, hence m * 2^13 <= 8191); a token of zeros gets
+ * e = 0.  The activations the method then works with are xhat = xq * 2^e.
+ */
+void tman_oracle_quantize_activations(const uint16_t *x, int N, int K, int16_t *xq, int32_t *e) {
+    for (int n = 0; n < N; ++n) {
+        double mx = 0.0;
+        for (int k = 0; k < K; ++k) {
+            double a = fabs(tman_oracle_half_to_double(x[(size_t)n * K + k]));
+            if (a > mx) mx = a;
+        }
+        int ex = 0;
+        if (mx > 0.0) {
+            int E;
+            (void)frexp(mx, &E);
+            ex = E - 13;
+        }
+        e[n] = ex;
+        for (int k = 0; k < K; ++k) {
+            double t = ldexp(tman_oracle_half_to_double(x[(size_t)n * K + k]), -ex); /* exact */
+            xq[(size_t)n * K + k] = (int16_t)nearbyint(t);                            /* ties to even */
+        }
+    }
+}
+
+/* The definition with real-valued (double) activations: Y[n][m] = sum_k xd[n][k] * Wd[m][k], as
+ * tman_oracle_matmul but for activations that are not fp16 numbers (the dequantized integer activations). */
+void tman_oracle_matmul_real_x(const uint8_t *q, const uint16_t *scale, const uint16_t *zero, const double *xd, int N,
+                               int M, int K, int group, int sign_mode, double *Y) {
+    int G = K / group;
+#pragma omp parallel
+    {
+        double *wd = (double *)malloc((size_t)K * sizeof(double));
+#pragma omp for schedule(static)
+        for (int m = 0; m < M; ++m) {
+            tman_oracle_dequant_row(q + (size_t)m * K, scale + (size_t)m * G, zero ? zero + (size_t)m * G : NULL, K,
+                                    group, sign_mode, wd);
+            for (int n = 0; n < N; ++n) {
+                double acc = 0.0;
+                for (int k = 0; k < K; ++k) acc += xd[(size_t)n * K + k] * wd[k];
+                Y[(size_t)n * M + m] = acc;
+            }
+        }
+        free(wd);
+    }
+}
+
+/* The table-lookup form on integer activations, step by step: 16-bit integer tables
+ *     Tq[n][j][p] = sum_{t<4} bit_t(p) * xq[n][4j+t]          (fits int16 by construction)
+ * looked up by the 4-bit weight patterns of every bit plane, shifted by the plane's position and accumulated
+ * as integers inside one quantization block,
+ *     A[n][m][G] = sum_i 2^i sum_{j in G} Tq[n][j][idx_i[m][j]],   Sq[n][G] = sum_{k in G} xq[n][k]
+ * and only then scaled in floating point:
+ *     Y[n][m] = 2^e[n] * sum_G scale[m][G] * ( A[n][m][G] - zero[m][G] * Sq[n][G] )
+ * (sign mode: scale * (2 A - Sq)).  block_sums, if non-NULL, receives A as 64-bit integers [N][M][K/group].
+ * Returns 0, or 1 if a table entry would not fit 16 bits (it cannot, for quantizer output). */
+int tman_oracle_lut_matmul_i16(const uint8_t *q, const uint16_t *scale, const uint16_t *zero, const int16_t *xq,
+                               const int32_t *e, int N, int M, int K, int bits, int group, int sign_mode, double *Y,
+                               int64_t *block_sums) {
+    const int g = 4;
+    int J = K / g, G = K / group, jpg = group / g, overflow = 0;
+    int16_t *T = (int16_t *)malloc((size_t)N * J * 16 * sizeof(int16_t));
+    uint8_t *idx = (uint8_t *)malloc((size_t)bits * M * J);
+    for (int n = 0; n < N; ++n)
+        for (int j = 0; j < J; ++j)
+            for (int p = 0; p < 16; ++p) {
+                int32_t acc = 0;
+                for (int t = 0; t < g; ++t)
+                    if ((p >> t) & 1) acc += xq[(size_t)n * K + (size_t)g * j + t];
+                if (acc < -32768 || acc > 32767) overflow = 1;
+                T[((size_t)n * J + j) * 16 + p] = (int16_t)acc;
+            }
+    tman_oracle_lut_indices(q, M, K, bits, g, idx);
+    for (int n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            double y = 0.0;
+            for (int gq = 0; gq < G; ++gq) {
+                int64_t a = 0, sq = 0;
+                for (int i = 0; i < bits; ++i) {
+                    int64_t plane = 0;
+                    for (int j = gq * jpg; j < (gq + 1) * jpg; ++j)
+                        plane += T[((size_t)n * J + j) * 16 + idx[((size_t)i * M + m) * J + j]];
+                    a += plane * ((int64_t)1 << i); /* shift by the plane's bit position, then accumulate */
+                }
+                for (int k = gq * group; k < (gq + 1) * group; ++k) sq += xq[(size_t)n * K + k];
+                if (block_sums) block_sums[((size_t)n * M + m) * G + gq] = a;
+                double s = tman_oracle_half_to_double(scale[(size_t)m * G + gq]);
+                if (sign_mode) {
+                    y += s * (2.0 * (double)a - (double)sq);
+                } else {
+                    double z = tman_oracle_half_to_double(zero[(size_t)m * G + gq]);
+                    y += s * ((double)a - z * (double)sq);
+                }
+            }
+            Y[(size_t)n * M + m] = ldexp(y, e[n]);
+        }
+    free(T);
+    free(idx);
+    return overflow;
+}
