@@ -146,6 +146,33 @@ int tman_mpgemv_batch_prepare(int32_t count, const tman_shape_t *shapes, const v
 int tman_mpgemv_batch_run(int32_t count, const tman_shape_t *shapes, int32_t N, const void *desc, void *stream);
 
 /*
+ * Integer activations and integer tables (Sec. 6.1 "A_INT16"; Sec. 4.3 two-level tiling: looked-up entries are
+ * aggregated at low precision inside a quantization block, in floating point only across blocks; Sec. 5: 16-bit
+ * table entries).  The paper gives no quantizer; this library's reading: token n gets the power-of-two step
+ * 2^e[n], the smallest with max_k |x[n][k]| / 2^e[n] <= 8191, and integer activations
+ * xq[n][k] = round_to_nearest_even(x[n][k] / 2^e[n]) -- 14-bit magnitudes, so that every table entry
+ *   Tq[n][j][p] = sum_{t<4, bit t of p} xq[n][4j+t]
+ * is an exact 16-bit integer.  tman_mpgemv_i16 then computes
+ *   y[n][m] = 2^e[n] * sum_G scale[m][G] * ( sum_i 2^i sum_{j in G} Tq[n][j][idx_i[m][j]] - zero[m][G] * Sq[n][G] )
+ * with the inner sums and Sq[n][G] = sum_{k in G} xq[n][k] as exact integers (sign form: scale * (2 sum - Sq)), the
+ * scales applied in fp32, fp16 result: the exact product of the weights with the activations xq * 2^e up to the
+ * fp32 sum across blocks and the final rounding.  Activations must be finite.
+ *   tman_build_lut_i16 : x fp16 [N][K], 1 <= N <= 8 -> lut (tman_lut_i16_bytes(N, K, group) bytes, 16-byte
+ *                        aligned): int16 entries laid out as the fp16 tables, int32 block sums, int32 e[n].
+ *                        The _batch form follows tman_build_lut_batch.
+ *   tman_mpgemv_i16    : arguments, workspace rules and determinism of tman_mpgemv, `lut` from tman_build_lut_i16.
+ *   tman_mpgemv_i16_batch_run : launches a batch whose descriptor table tman_mpgemv_batch_prepare wrote with
+ *                        integer table buffers in `lut` (the two table buffers have the same geometry).
+ */
+size_t tman_lut_i16_bytes(int32_t N, int32_t K, int32_t group);
+int tman_build_lut_i16(const void *x, int32_t N, int32_t K, int32_t group, void *lut, void *stream);
+int tman_build_lut_i16_batch(int32_t count, const void *const *x, int32_t N, const int32_t *K, int32_t group,
+                             void *const *lut, void *stream);
+int tman_mpgemv_i16(const tman_shape_t *shape, const void *packed, const void *lut, int32_t N, void *y, void *workspace,
+                    size_t workspace_bytes, void *stream);
+int tman_mpgemv_i16_batch_run(int32_t count, const tman_shape_t *shapes, int32_t N, const void *desc, void *stream);
+
+/*
  * Decoding mpGEMV of ONE token with the table precompute inside the lookup kernel (Sec. 2.2, Sec. 4.3 for
  * the lookups; Sec. 5 moves the precompute into a kernel of its own because it is costly on the paper's
  * hardware, whereas here a kernel boundary costs more than the precompute).  Every workgroup builds the

@@ -74,6 +74,16 @@ def _load():
         L.tman_build_lut_batch.argtypes = [C.c_int32, vp, C.c_int32, vp, C.c_int32, vp, vp]
         L.tman_mpgemv.restype = C.c_int
         L.tman_mpgemv.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.tman_lut_i16_bytes.restype = C.c_size_t
+        L.tman_lut_i16_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+        L.tman_build_lut_i16.restype = C.c_int
+        L.tman_build_lut_i16.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, vp, vp]
+        L.tman_build_lut_i16_batch.restype = C.c_int
+        L.tman_build_lut_i16_batch.argtypes = [C.c_int32, vp, C.c_int32, vp, C.c_int32, vp, vp]
+        L.tman_mpgemv_i16.restype = C.c_int
+        L.tman_mpgemv_i16.argtypes = [sp, vp, vp, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.tman_mpgemv_i16_batch_run.restype = C.c_int
+        L.tman_mpgemv_i16_batch_run.argtypes = [C.c_int32, sp, C.c_int32, vp, vp]
         L.tman_mpgemv_batch_desc_bytes.restype = C.c_size_t
         L.tman_mpgemv_batch_desc_bytes.argtypes = [C.c_int32]
         L.tman_mpgemv_batch_prepare.restype = C.c_int
@@ -179,6 +189,35 @@ def tman_unpack_weights(shape: Shape, packed, codes, scales=None, zeros=None, st
 def tman_build_lut(x, N: int, K: int, group: int, lut, stream=None) -> None:
     """x fp16 [N][K] -> lut (u8 buffer of tman_lut_bytes(N, K, group))."""
     _check(_load().tman_build_lut(_ptr(x), N, K, group, _ptr(lut), _stream(stream)), "tman_build_lut")
+
+
+def tman_lut_i16_bytes(N: int, K: int, group: int) -> int:
+    return int(_load().tman_lut_i16_bytes(N, K, group))
+
+
+def tman_build_lut_i16(x, N: int, K: int, group: int, lut, stream=None) -> None:
+    """x fp16 [N][K] -> integer tables (u8 buffer of tman_lut_i16_bytes(N, K, group))."""
+    _check(_load().tman_build_lut_i16(_ptr(x), N, K, group, _ptr(lut), _stream(stream)), "tman_build_lut_i16")
+
+
+def tman_build_lut_i16_batch(xs, N: int, Ks, group: int, luts, stream=None) -> None:
+    n = len(xs)
+    vp = C.c_void_p * n
+    _check(_load().tman_build_lut_i16_batch(n, vp(*[_ptr(t) for t in xs]), N, (C.c_int32 * n)(*Ks), group,
+                                            vp(*[_ptr(t) for t in luts]), _stream(stream)), "tman_build_lut_i16_batch")
+
+
+def tman_mpgemv_i16(shape: Shape, packed, lut, N: int, y, workspace, stream=None) -> None:
+    """y fp16 [N][M] through lookups in integer tables (from tman_build_lut_i16)."""
+    wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
+    _check(_load().tman_mpgemv_i16(C.byref(shape.c()), _ptr(packed), _ptr(lut), N, _ptr(y), _ptr(workspace), wb,
+                                   _stream(stream)), "tman_mpgemv_i16")
+
+
+def tman_mpgemv_i16_batch_run(shapes, N: int, desc, stream=None) -> None:
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    _check(_load().tman_mpgemv_i16_batch_run(n, cs, N, _ptr(desc), _stream(stream)), "tman_mpgemv_i16_batch_run")
 
 
 def tman_mpgemv(shape: Shape, packed, lut, N: int, y, workspace, stream=None) -> None:

@@ -49,6 +49,11 @@ size_t tman_lut_bytes(int32_t N, int32_t K, int32_t group) {
     return nkt * kTableBytesPerKTile * np + nkt * (kKTile / group) * np * sizeof(float);
 }
 
+size_t tman_lut_i16_bytes(int32_t N, int32_t K, int32_t group) {
+    const size_t b = tman_lut_bytes(N, K, group);  // 16-bit entries and 32-bit block sums, as the fp16 tables
+    return b ? b + 32 : 0;                          // + the tokens' exponents (8 x int32)
+}
+
 size_t tman_mpgemv_workspace_bytes(const tman_shape_t* shape, int32_t N) {
     if (check_shape(shape) != TMAN_OK || N < 1 || N > TMAN_MAX_DECODE_TOKENS) return 0;
     const Layout L = make_layout(shape);
@@ -109,6 +114,40 @@ int tman_build_lut_batch(int32_t count, const void* const* x, int32_t N, const i
         if (!aligned16(lut[i])) return TMAN_ERR_ALIGN;
     }
     return launch_build_lut_batch(count, x, N, K, group, lut, (hipStream_t)stream);
+}
+
+int tman_build_lut_i16(const void* x, int32_t N, int32_t K, int32_t group, void* lut, void* stream) {
+    if (!x || !lut) return TMAN_ERR_NULL;
+    if (group != 32 && group != 64 && group != 128) return TMAN_ERR_GROUP;
+    if (N < 1 || N > TMAN_MAX_DECODE_TOKENS || K < 1 || K % group != 0) return TMAN_ERR_SHAPE;
+    if (!aligned16(lut)) return TMAN_ERR_ALIGN;
+    return launch_build_lut_i16_batch(1, &x, N, &K, group, &lut, (hipStream_t)stream);
+}
+
+int tman_build_lut_i16_batch(int32_t count, const void* const* x, int32_t N, const int32_t* K, int32_t group,
+                             void* const* lut, void* stream) {
+    if (!x || !K || !lut) return TMAN_ERR_NULL;
+    if (group != 32 && group != 64 && group != 128) return TMAN_ERR_GROUP;
+    if (count < 1 || count > TMAN_MAX_BATCH || N < 1 || N > TMAN_MAX_DECODE_TOKENS) return TMAN_ERR_SHAPE;
+    for (int i = 0; i < count; ++i) {
+        if (!x[i] || !lut[i]) return TMAN_ERR_NULL;
+        if (K[i] < 1 || K[i] % group != 0) return TMAN_ERR_SHAPE;
+        if (!aligned16(lut[i])) return TMAN_ERR_ALIGN;
+    }
+    return launch_build_lut_i16_batch(count, x, N, K, group, lut, (hipStream_t)stream);
+}
+
+int tman_mpgemv_i16(const tman_shape_t* shape, const void* packed, const void* lut, int32_t N, void* y, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc != TMAN_OK) return rc;
+    if (!packed || !lut || !y) return TMAN_ERR_NULL;
+    if (N < 1 || N > TMAN_MAX_DECODE_TOKENS) return TMAN_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(lut)) return TMAN_ERR_ALIGN;
+    size_t need = tman_mpgemv_workspace_bytes(shape, N);
+    if (need && (!workspace || workspace_bytes < need)) return TMAN_ERR_WORKSPACE;
+    if (workspace && !aligned16(workspace)) return TMAN_ERR_ALIGN;
+    return launch_mpgemv_i16(make_layout(shape), packed, lut, N, y, workspace, (hipStream_t)stream);
 }
 
 int tman_mpgemv(const tman_shape_t* shape, const void* packed, const void* lut, int32_t N, void* y, void* workspace,
@@ -181,6 +220,20 @@ int tman_mpgemv_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, 
     }
     return launch_mpgemv_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO, N,
                                static_cast<const GemvDesc*>(desc), count, max_wg, (hipStream_t)stream);
+}
+
+int tman_mpgemv_i16_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, const void* desc, void* stream) {
+    int rc = check_batch(count, shapes, N);
+    if (rc != TMAN_OK) return rc;
+    if (!desc) return TMAN_ERR_NULL;
+    if (!aligned16(desc)) return TMAN_ERR_ALIGN;
+    int max_wg = 0;
+    for (int i = 0; i < count; ++i) {
+        const int n = plan_gemv(make_layout(&shapes[i]), N).n_workgroups;
+        if (n > max_wg) max_wg = n;
+    }
+    return launch_mpgemv_i16_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO, N,
+                                   static_cast<const GemvDesc*>(desc), count, max_wg, (hipStream_t)stream);
 }
 
 int tman_mpgemv_x(const tman_shape_t* shape, const void* packed, const void* x, void* y, void* workspace,

@@ -257,9 +257,10 @@ __device__ __forceinline__ const GemvDesc& desc_of(const KernelArgs<SINGLE>& a, 
 }
 
 // Output of one row block by its first wave: y holds the sums of the workgroup's K segment for the lane's
-// row.  With one segment they are the result; otherwise the segments meet through memory (see above).
+// row; `step` is a factor per token applied to the final sum (1, or the power-of-two step of integer tables).  With one segment they are the result; otherwise the segments meet through memory (see above).
 template <int NP>
-__device__ __forceinline__ void finish_rows(const GemvDesc& d, int rb, int seg, int n_seg, int lane, float (&y)[NP]) {
+__device__ __forceinline__ void finish_rows(const GemvDesc& d, int rb, int seg, int n_seg, int lane, float (&y)[NP],
+                                            const float (&step)[NP]) {
     const int m = rb * kRows + lane;
     const int M = d.M, N = d.N;
     _Float16* out = static_cast<_Float16*>(d.y);
@@ -267,7 +268,7 @@ __device__ __forceinline__ void finish_rows(const GemvDesc& d, int rb, int seg, 
         if (m < M) {
 #pragma unroll
             for (int n = 0; n < NP; ++n)
-                if (n < N) out[(size_t)n * M + m] = (_Float16)y[n];
+                if (n < N) out[(size_t)n * M + m] = (_Float16)(y[n] * step[n]);
         }
         return;
     }
@@ -305,7 +306,7 @@ __device__ __forceinline__ void finish_rows(const GemvDesc& d, int rb, int seg, 
     if (m < M) {
 #pragma unroll
         for (int n = 0; n < NP; ++n)
-            if (n < N) out[(size_t)n * M + m] = (_Float16)acc[n];
+            if (n < N) out[(size_t)n * M + m] = (_Float16)(acc[n] * step[n]);
     }
     if (lane == 0) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

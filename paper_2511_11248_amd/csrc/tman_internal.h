@@ -122,6 +122,11 @@ int launch_unpack(const Layout& L, const void* packed, uint8_t* codes, void* sca
 int launch_build_lut(const void* x, int N, int K, int group, void* lut, hipStream_t st);
 int launch_build_lut_batch(int count, const void* const* x, int N, const int* K, int group, void* const* lut,
                            hipStream_t st);
+int launch_build_lut_i16_batch(int count, const void* const* x, int N, const int* K, int group, void* const* lut,
+                               hipStream_t st);
+int launch_mpgemv_i16(const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace, hipStream_t st);
+int launch_mpgemv_i16_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,
+                            int max_workgroups, hipStream_t st);
 int launch_mpgemv(const Layout& L, const void* packed, const void* lut, int N, void* y, void* workspace,
                   hipStream_t st);
 int launch_mpgemv_batch(int bits, int group, int has_zero, int N, const GemvDesc* descs_dev, int n_gemv,

@@ -162,7 +162,8 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
     y = ((load_lds<float>(lr + lane * 4) + load_lds<float>(lr + (kRows + lane) * 4)) +
          load_lds<float>(lr + (2 * kRows + lane) * 4)) + load_lds<float>(lr + (3 * kRows + lane) * 4);
     float yy[1] = {y};
-    finish_rows<1>(d, rb, seg, n_seg, lane, yy);
+    const float one[1] = {1.f};
+    finish_rows<1>(d, rb, seg, n_seg, lane, yy, one);
 }
 
 // ---------------------------------------------------------------------------------------------
