@@ -124,6 +124,17 @@ def decode_job(torch, tman, synth, dev, w, N, n_inst):
             x_descs.append(d)
         torch.cuda.synchronize()
         x_calls = [tman.bound_mpgemv_x_batch_run(shapes, x_descs[inst]) for inst in range(n_inst)]
+    # integer tables (A_INT16 reading): a table launch that quantizes the activations, a lookup launch on int16 entries
+    i16_luts = [torch.empty(tman.tman_lut_i16_bytes(N, w.layers[li0].K, w.group), dtype=torch.uint8, device=dev)
+                for li0 in act_layer0]
+    i16_descs = []
+    for inst in range(n_inst):
+        d = torch.empty(tman.tman_mpgemv_batch_desc_bytes(len(shapes)), dtype=torch.uint8, device=dev)
+        tman.tman_mpgemv_batch_prepare(shapes, blobs[inst], [i16_luts[a] for a in act_of_layer], N, ys, wss, d)
+        i16_descs.append(d)
+    torch.cuda.synchronize()
+    i16_lut_calls = [tman.bound_build_lut_i16_batch(xs[inst], N, Ks, w.group, i16_luts) for inst in range(n_inst)]
+    i16_gemv_calls = [tman.bound_mpgemv_i16_batch_run(shapes, N, i16_descs[inst]) for inst in range(n_inst)]
     # a few tokens: the same product on the matrix cores (tman_mpgemm's small-batch kernel), one launch per layer set
     mm_calls, mm_keep = None, []
     if N > 1:
@@ -140,7 +151,8 @@ def decode_job(torch, tman, synth, dev, w, N, n_inst):
         mm_keep.append(mm_ws)
     return {"shapes": shapes, "acts": acts, "weight_bytes_per_step": weight_bytes_per_step, "ys": ys,
             "lut_calls": lut_calls, "gemv_calls": gemv_calls, "x_calls": x_calls, "mm_calls": mm_calls, "stream": stream,
-            "keep": (blobs, xs, luts, wss, descs, x_descs, mm_keep)}  # the launches hold raw pointers into these
+            "i16_lut_calls": i16_lut_calls, "i16_gemv_calls": i16_gemv_calls,
+            "keep": (blobs, xs, luts, wss, descs, x_descs, mm_keep, i16_luts, i16_descs)}  # the launches hold raw pointers into these
 
 
 def timed_steps(torch, step, warm, steps):
@@ -155,8 +167,14 @@ def timed_steps(torch, step, warm, steps):
     return (time.perf_counter() - t0) / steps
 
 
-def decode_step_fn(job, n_inst, matrix_cores=False):
+def decode_step_fn(job, n_inst, matrix_cores=False, integer_tables=False):
     stream = job["stream"]
+    if integer_tables:  # activations quantized to integers, int16 tables, integer sums inside a quantization block
+        def ints(i):
+            job["i16_lut_calls"][i % n_inst](stream)
+            job["i16_gemv_calls"][i % n_inst](stream)
+
+        return ints
     if matrix_cores:  # a few tokens, dequantized in registers and multiplied on the matrix cores: one launch
         return lambda i: job["mm_calls"][i % n_inst](stream)
     if job["x_calls"] is not None:  # one token: one launch
@@ -169,19 +187,23 @@ def decode_step_fn(job, n_inst, matrix_cores=False):
     return two
 
 
-def decode_error(torch, synth, oracle, w, job, N, inst=0, matrix_cores=False):
-    """Largest row-normalised error of the outputs of the step on copy `inst` against the fp64 oracle, and the
-    oracle's time."""
+def decode_error(torch, synth, oracle, w, job, N, inst=0, matrix_cores=False, integer_tables=False):
+    """Largest row-normalised error of the outputs of the step on copy `inst` against the fp64 oracle (with integer
+    tables: the oracle for the integer activations), and the oracle's time."""
     for y in job["ys"]:
         y.fill_(float("nan"))
-    decode_step_fn(job, max(inst + 1, 1), matrix_cores)(inst)
+    decode_step_fn(job, max(inst + 1, 1), matrix_cores, integer_tables)(inst)
     torch.cuda.synchronize()
     err, cpu_t, used = 0.0, 0.0, 1
     for li in range(len(job["shapes"])):
         q, sc, z = synth.layer_tensors(w, inst, li)
         xh = synth.activation(w, inst, li, N)
         c0 = time.perf_counter()
-        Y, used = oracle.matmul(q, sc, z, xh, w.bits, w.group, return_threads=True)
+        if integer_tables:
+            xq, ex = oracle.quantize_activations(xh)
+            Y = oracle.matmul_real_x(q, sc, z, xq.astype(np.float64) * (2.0 ** ex.astype(np.float64))[:, None], w.bits, w.group)
+        else:
+            Y, used = oracle.matmul(q, sc, z, xh, w.bits, w.group, return_threads=True)
         cpu_t += time.perf_counter() - c0
         err = max(err, float(oracle.row_relative_error(job["ys"][li].cpu().numpy().astype(np.float64), Y).max()))
     return err, cpu_t, used
@@ -225,6 +247,14 @@ def other_configs(args, torch, tman, synth, oracle, dev):
             kind = "one launch per layer set" if job["x_calls"] is not None else "table launch + lookup launch per layer set"
             add(f"{name} N={N}, {w.instances} rotating copies, {kind}" + (" (cache-resident: correctness only)" if w.instances == 1 else ""),
                 sec, gbs, "GB/s", HBM_PEAK_GBS, err, "all outputs of copy 0")
+            if w.config == 2:  # integer activations and tables (the paper's A_INT16 configuration), same workload
+                step = decode_step_fn(job, w.instances, integer_tables=True)
+                sec = timed_steps(torch, step, 100, 300)
+                err, _, _ = decode_error(torch, synth, oracle, w, job, N, integer_tables=True)
+                add(f"{name} N={N}, {w.instances} rotating copies, integer tables (tman_build_lut_i16 launch + "
+                    f"tman_mpgemv_i16 launch per layer set); error against the oracle for the integer activations, "
+                    f"bound 1e-3", sec, job["weight_bytes_per_step"] / sec / 1e9, "GB/s", HBM_PEAK_GBS, err,
+                    "all outputs of copy 0")
             if N > 1:  # the same tokens through the matrix-core kernel
                 step = decode_step_fn(job, w.instances, matrix_cores=True)
                 sec = timed_steps(torch, step, 100, 300)

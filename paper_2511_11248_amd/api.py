@@ -351,6 +351,29 @@ def bound_build_lut_batch(xs, N: int, Ks, group: int, luts):
     return call
 
 
+def bound_build_lut_i16_batch(xs, N: int, Ks, group: int, luts):
+    n = len(xs)
+    vp = C.c_void_p * n
+    fn, args = _load().tman_build_lut_i16_batch, (n, vp(*[_ptr(t) for t in xs]), N, (C.c_int32 * n)(*Ks), group,
+                                                   vp(*[_ptr(t) for t in luts]))
+
+    def call(stream_handle):
+        _check(fn(*args, stream_handle), "tman_build_lut_i16_batch")
+
+    return call
+
+
+def bound_mpgemv_i16_batch_run(shapes, N: int, desc):
+    n = len(shapes)
+    cs = (_CShape * n)(*[s.c() for s in shapes])
+    fn, args = _load().tman_mpgemv_i16_batch_run, (n, cs, N, _ptr(desc))
+
+    def call(stream_handle):
+        _check(fn(*args, stream_handle), "tman_mpgemv_i16_batch_run")
+
+    return call
+
+
 def bound_mpgemv_batch_run(shapes, N: int, desc):
     n = len(shapes)
     cs = (_CShape * n)(*[s.c() for s in shapes])

@@ -137,8 +137,24 @@ __global__ void __launch_bounds__(256) build_lut_i16_kernel(LutJobs a) {
     const uint16_t* xb = reinterpret_cast<const uint16_t*>(jb.x) + (size_t)n * K;
     // magnitudes compare like their bit patterns
     unsigned mx = 0;
-    if (n < N)
-        for (int k = threadIdx.x; k < K; k += 256) mx = max(mx, (unsigned)(xb[k] & 0x7fffu));
+    if (n < N) {
+        // 16 bytes per thread and step where the row allows it (K is a multiple of 32; the row start is 16-byte
+        // aligned when x is and K * 2 is a multiple of 16, which it is)
+        if ((reinterpret_cast<uintptr_t>(xb) & 15u) == 0) {
+            typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+            const u32x4_t* x16 = reinterpret_cast<const u32x4_t*>(xb);
+            for (int c = threadIdx.x; c < K / 8; c += 256) {
+                const u32x4_t w = x16[c];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t d = w[i] & 0x7fff7fffu;
+                    mx = max(mx, max(d & 0xffffu, d >> 16));
+                }
+            }
+        } else {
+            for (int k = threadIdx.x; k < K; k += 256) mx = max(mx, (unsigned)(xb[k] & 0x7fffu));
+        }
+    }
     for (int d = 1; d < 64; d <<= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, d, 64));
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = mx;
     __syncthreads();
