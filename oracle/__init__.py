@@ -11,6 +11,8 @@ from .oracle import (  # noqa: F401
     quantize_activations,
     matmul_real_x,
     lut_matmul_i16,
+    quantize_activations_i8,
+    matmul_i8,
     table_dequant_matmul,
     build_tables,
     lut_indices,

@@ -59,6 +59,11 @@ def lib():
         L.tman_oracle_matmul_real_x.argtypes = [u8p, u16p, u16p, f64p] + [C.c_int] * 5 + [f64p]
         L.tman_oracle_lut_matmul_i16.restype = C.c_int
         L.tman_oracle_lut_matmul_i16.argtypes = [u8p, u16p, u16p, i16p, i32p] + [C.c_int] * 6 + [f64p, i64p]
+        i8p, f32p = C.POINTER(C.c_int8), C.POINTER(C.c_float)
+        L.tman_oracle_quantize_activations_i8.restype = None
+        L.tman_oracle_quantize_activations_i8.argtypes = [u16p, C.c_int, C.c_int, i8p, f32p]
+        L.tman_oracle_matmul_i8.restype = None
+        L.tman_oracle_matmul_i8.argtypes = [u8p, u16p, u16p, i8p, f32p] + [C.c_int] * 4 + [i64p, f64p]
         _lib = L
     return _lib
 
@@ -150,6 +155,34 @@ def lut_matmul_i16(q, scale, zero, xq, e, bits: int, group: int, return_block_su
                                             _p(A, C.c_int64))
     assert over == 0, "a table entry does not fit 16 bits"
     return (Y, A) if return_block_sums else Y
+
+
+def quantize_activations_i8(x):
+    """Per-token absmax quantizer to int8 (decision in binary32): (xq int8 [N][K], absmax float32 [N])."""
+    x = np.ascontiguousarray(x, dtype=np.float16)
+    N, K = x.shape
+    xq = np.empty((N, K), dtype=np.int8)
+    mx = np.empty(N, dtype=np.float32)
+    lib().tman_oracle_quantize_activations_i8(_p(x.view(np.uint16), C.c_uint16), N, K, _p(xq, C.c_int8), _p(mx, C.c_float))
+    return xq, mx
+
+
+def matmul_i8(q, row_scale, row_zero, xq, absmax, bits: int):
+    """Integer product of codes and int8 activations with one scale / zero per row: (acc int64 [N][M], Y [N][M])."""
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    M, K = q.shape
+    assert int(q.max(initial=0)) < (1 << bits)
+    xq = np.ascontiguousarray(xq, dtype=np.int8)
+    N = xq.shape[0]
+    assert xq.shape == (N, K)
+    rs = np.ascontiguousarray(row_scale, dtype=np.float16).reshape(M).view(np.uint16)
+    rz = None if row_zero is None else np.ascontiguousarray(row_zero, dtype=np.float16).reshape(M).view(np.uint16)
+    mx = np.ascontiguousarray(absmax, dtype=np.float32)
+    acc = np.empty((N, M), dtype=np.int64)
+    Y = np.empty((N, M), dtype=np.float64)
+    lib().tman_oracle_matmul_i8(_p(q, C.c_uint8), _p(rs, C.c_uint16), _p(rz, C.c_uint16), _p(xq, C.c_int8), _p(mx, C.c_float),
+                                N, M, K, int(row_zero is None), _p(acc, C.c_int64), _p(Y, C.c_double))
+    return acc, Y
 
 
 def build_tables(x, g: int = 4) -> np.ndarray:

@@ -362,3 +362,56 @@ int tman_oracle_lut_matmul_i16(const uint8_t *q, const uint16_t *scale, const ui
     free(idx);
     return overflow;
 }
+
+/* ------------------------------------------------------------------------------------------------
+ * Per-channel / per-tensor formats on an integer matrix unit (Sec. 6.1: BitNet's ternary weights with one
+ * scale per tensor, treated as 2-bit; Sec. 6.2 mpGEMM: such models are dequantized to INT8 and computed as
+ * W_INT8 x A_INT8).
+ *
+ * Reading used here (the paper gives no activation quantizer; this is the per-token absmax quantizer of the
+ * BitNet family): token n has the step delta[n] = max_k |x[n][k]| / 127 and integer activations
+ *     xq[n][k] = round_to_nearest_even( x[n][k] * (127 / max) ),   |xq| <= 127,
+ * the decision taken in binary32 arithmetic as the kernel takes it: inv = 127.0f / max (one correctly rounded
+ * division), t = x * inv (one correctly rounded product), xq = rint(t).  A token of zeros has delta = 0.
+ */
+void tman_oracle_quantize_activations_i8(const uint16_t *x, int N, int K, int8_t *xq, float *absmax) {
+    for (int n = 0; n < N; ++n) {
+        float mx = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            float a = fabsf((float)tman_oracle_half_to_double(x[(size_t)n * K + k]));
+            if (a > mx) mx = a;
+        }
+        absmax[n] = mx;
+        volatile float inv = mx > 0.0f ? 127.0f / mx : 0.0f; /* volatile: no excess precision, no reassociation */
+        for (int k = 0; k < K; ++k) {
+            volatile float t = (float)tman_oracle_half_to_double(x[(size_t)n * K + k]) * inv;
+            xq[(size_t)n * K + k] = (int8_t)nearbyintf(t);
+        }
+    }
+}
+
+/* Integer product and its scaling: with the weights' codes c[m][k] (unsigned, below 2^bits), ONE scale s[m] and
+ * zero z[m] per row (a per-tensor format repeats the same pair for every row):
+ *     acc[n][m] = sum_k c[m][k] * xq[n][k]                      exact integer
+ *     Y[n][m]   = s[m] * (absmax[n] / 127) * ( acc[n][m] - z[m] * sum_k xq[n][k] )
+ * (sign form: s * delta * (2 acc - sum xq)).  acc is int64 [N][M]; Y double [N][M]. */
+void tman_oracle_matmul_i8(const uint8_t *q, const uint16_t *row_scale, const uint16_t *row_zero, const int8_t *xq,
+                           const float *absmax, int N, int M, int K, int sign_mode, int64_t *acc, double *Y) {
+    for (int n = 0; n < N; ++n) {
+        int64_t sx = 0;
+        for (int k = 0; k < K; ++k) sx += xq[(size_t)n * K + k];
+        double delta = (double)absmax[n] / 127.0;
+        for (int m = 0; m < M; ++m) {
+            int64_t a = 0;
+            for (int k = 0; k < K; ++k) a += (int64_t)q[(size_t)m * K + k] * (int64_t)xq[(size_t)n * K + k];
+            acc[(size_t)n * M + m] = a;
+            double s = tman_oracle_half_to_double(row_scale[m]);
+            if (sign_mode) {
+                Y[(size_t)n * M + m] = s * delta * (2.0 * (double)a - (double)sx);
+            } else {
+                double z = tman_oracle_half_to_double(row_zero[m]);
+                Y[(size_t)n * M + m] = s * delta * ((double)a - z * (double)sx);
+            }
+        }
+    }
+}
