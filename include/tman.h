@@ -241,6 +241,30 @@ int tman_mpgemm_batch_prepare(int32_t count, const tman_shape_t *shapes, const v
 int tman_mpgemm_batch_run(int32_t count, const tman_shape_t *shapes, int32_t N, const void *desc, void *stream);
 
 /*
+ * mpGEMM on the INTEGER matrix cores for weights with one scale and one zero per row of W: per-channel formats,
+ * and per-tensor ones such as BitNet's ternary weights as 2-bit codes (Sec. 6.1: "per-tensor quantization ...
+ * treated as 2-bit"; Sec. 6.2 mpGEMM: "we dequantize to INT8 and perform computation with W_INT8 A_INT8").
+ * The packed blob is the ordinary one; the call uses the scale and zero of the FIRST quantization block of every
+ * row for the whole row, so it computes y = x * dequant(W)^T only for blobs whose rows repeat one (scale, zero)
+ * pair over all their blocks (not checked).
+ *   tman_quantize_act_i8 : x fp16 [N][K] (finite) -> xq, tman_act_i8_bytes(N, K) bytes, 16-byte aligned:
+ *       per-token absmax quantization (the paper gives no quantizer; this is the one of the BitNet family):
+ *       xq[n][k] = round_to_nearest_even(x[n][k] * (127 / max_k |x[n][k]|)), the decision taken in binary32
+ *       (inv = 127.0f / max correctly rounded, t = x * inv correctly rounded, rint), stored as int8 [N][K] with
+ *       every 32-column group permuted (byte p = 8 o + 4 h + b of a group holds column 8 b + 4 h + o; o < 4,
+ *       h < 2, b < 4: the order in which the weights' codes leave the bit-plane transposition), then, each on a
+ *       256-byte boundary, float max[N] and int32 sum_k xq[n][k].
+ *   tman_mpgemm_i8 : acc[n][m] = sum_k code[m][k] * xq[n][k] on v_mfma_i32_32x32x32_i8 (exact), then
+ *       y[n][m] = fp16( scale[m] * max[n] / 127 * (acc[n][m] - zero[m] * sum_k xq[n][k]) )   (sign form:
+ *       scale * max / 127 * (2 acc - sum)), the scaling in fp32.  `acc`, if not NULL, receives the integer
+ *       accumulators, int32 [N][M] (test aid).  Any N >= 1; K a multiple of 32; N * K < 2^32.
+ */
+size_t tman_act_i8_bytes(int32_t N, int32_t K);
+int tman_quantize_act_i8(const void *x, int32_t N, int32_t K, void *xq, void *stream);
+int tman_mpgemm_i8(const tman_shape_t *shape, const void *packed, const void *xq, int32_t N, void *y, int32_t *acc,
+                   void *stream);
+
+/*
  * Rows of W (output features) one workgroup of tman_mpgemm's tiled kernel covers for this shape and N: 64, 128, 192 or 256,
  * chosen so that the workgroups fill the compute units of the current device best (256 units are
  * assumed when no device is present).  Informational; 0 for an invalid shape or N < 1.

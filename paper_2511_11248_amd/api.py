@@ -102,6 +102,12 @@ def _load():
         L.tman_mpgemm_batch_prepare.argtypes = [C.c_int32, sp, vp, vp, C.c_int32, vp, vp, vp, vp, vp]
         L.tman_mpgemm_batch_run.restype = C.c_int
         L.tman_mpgemm_batch_run.argtypes = [C.c_int32, sp, C.c_int32, vp, vp]
+        L.tman_act_i8_bytes.restype = C.c_size_t
+        L.tman_act_i8_bytes.argtypes = [C.c_int32, C.c_int32]
+        L.tman_quantize_act_i8.restype = C.c_int
+        L.tman_quantize_act_i8.argtypes = [vp, C.c_int32, C.c_int32, vp, vp]
+        L.tman_mpgemm_i8.restype = C.c_int
+        L.tman_mpgemm_i8.argtypes = [sp, vp, vp, C.c_int32, vp, vp, vp]
         L.tman_mpgemm_tile_rows.restype = C.c_int32
         L.tman_mpgemm_tile_rows.argtypes = [sp, C.c_int32]
         L.tman_check_packed.restype = C.c_int
@@ -252,6 +258,21 @@ def tman_mpgemm(shape: Shape, packed, x, N: int, y, workspace=None, stream=None)
     wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
     _check(_load().tman_mpgemm(C.byref(shape.c()), _ptr(packed), _ptr(x), N, _ptr(y), _ptr(workspace), wb,
                                _stream(stream)), "tman_mpgemm")
+
+
+def tman_act_i8_bytes(N: int, K: int) -> int:
+    return int(_load().tman_act_i8_bytes(N, K))
+
+
+def tman_quantize_act_i8(x, N: int, K: int, xq, stream=None) -> None:
+    """x fp16 [N][K] -> int8 activations (permuted per 32 columns), per-token maxima and sums."""
+    _check(_load().tman_quantize_act_i8(_ptr(x), N, K, _ptr(xq), _stream(stream)), "tman_quantize_act_i8")
+
+
+def tman_mpgemm_i8(shape: Shape, packed, xq, N: int, y, acc=None, stream=None) -> None:
+    """y fp16 [N][M] on the integer matrix cores for weights with one scale and zero per row."""
+    _check(_load().tman_mpgemm_i8(C.byref(shape.c()), _ptr(packed), _ptr(xq), N, _ptr(y), _ptr(acc), _stream(stream)),
+           "tman_mpgemm_i8")
 
 
 def tman_mpgemm_batch_prepare(shapes, packed, xs, N: int, y, workspace, desc, stream=None) -> None:

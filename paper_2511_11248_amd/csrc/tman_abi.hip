@@ -347,6 +347,28 @@ int tman_mpgemm_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, 
                                      static_cast<const GemvDesc*>(desc), count, max_wg, (hipStream_t)stream);
 }
 
+size_t tman_act_i8_bytes(int32_t N, int32_t K) {
+    if (N < 1 || K < 1 || K % 32 != 0 || (long long)N * K > 0xFFFFFFF0LL) return 0;
+    return act_i8_bytes(N, K);
+}
+
+int tman_quantize_act_i8(const void* x, int32_t N, int32_t K, void* xq, void* stream) {
+    if (!x || !xq) return TMAN_ERR_NULL;
+    if (tman_act_i8_bytes(N, K) == 0) return TMAN_ERR_SHAPE;
+    if (!aligned16(xq)) return TMAN_ERR_ALIGN;
+    return launch_quantize_act_i8(x, N, K, xq, (hipStream_t)stream);
+}
+
+int tman_mpgemm_i8(const tman_shape_t* shape, const void* packed, const void* xq, int32_t N, void* y, int32_t* acc,
+                   void* stream) {
+    int rc = check_shape(shape);
+    if (rc != TMAN_OK) return rc;
+    if (!packed || !xq || !y) return TMAN_ERR_NULL;
+    if (tman_act_i8_bytes(N, shape->K) == 0) return TMAN_ERR_SHAPE;
+    if (!aligned16(packed) || !aligned16(xq)) return TMAN_ERR_ALIGN;
+    return launch_mpgemm_i8(make_layout(shape), packed, xq, N, y, acc, (hipStream_t)stream);
+}
+
 int tman_check_packed(const tman_shape_t* shape, const void* packed, void* stream) {
     int rc = check_shape(shape);
     if (rc != TMAN_OK) return rc;

@@ -1,0 +1,358 @@
+// mpGEMM on the integer matrix cores for formats with ONE scale and zero per row of W -- per-channel, or
+// per-tensor such as BitNet's ternary weights (Sec. 6.1: "per-tensor quantization ... treated as 2-bit";
+// Sec. 6.2 mpGEMM: such models are dequantized to INT8 and computed as W_INT8 x A_INT8).
+//
+//   xq[n][k]  = rint(x[n][k] * 127 / max_k |x[n][k]|)                      int8, per token (tman_quantize_act_i8)
+//   acc[n][m] = sum_k c[m][k] * xq[n][k]                                     int32, exact (v_mfma_i32_32x32x32_i8)
+//   y[n][m]   = scale[m] * (max_n / 127) * (acc[n][m] - zero[m] * sum_k xq[n][k])      fp32, rounded once to fp16
+//
+// Level 1 of the paper's dequantization (bit-serial -> bit-parallel) is all the weights need here: the matrix
+// unit multiplies the unsigned codes themselves, the zero point moves to the epilogue through the token's sum of
+// integer activations.  The codes of a 32-weight block come out of the bit-field transposition as four words
+// of eight nibbles, word o nibble f = weight 4 f + o; two masks per word turn them into bytes in the order
+//   position p = 8 o + 4 h + b  <->  column 8 b + 4 h + o          (o < 4, h < 2, b < 4)
+// and instead of sorting the weights the ACTIVATIONS are stored in that order: the quantizer writes every
+// 32-column group of a token permuted accordingly, so both MFMA operands are plain 16-byte LDS reads.
+//
+// Workgroup = 4 waves = 128 rows x 128 tokens; wave (wm, wn) accumulates 64 x 64 as four 32 x 32 tiles.  Per
+// 64-column stage every wave transposes one 32-weight block of one of the two row blocks into LDS (lane = row),
+// the 128 x 64 bytes of activations go through registers into LDS, one barrier, eight MFMAs per wave.  Two stage
+// buffers: a wave writes stage s + 1 while others still read stage s.
+#include <hip/hip_fp16.h>
+
+#include <mutex>
+
+#include "tman_dequant_device.h"
+
+namespace tman {
+
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+constexpr int kI8Rows = 128, kI8Tokens = 128, kI8StageK = 64;
+constexpr int kI8RowBytes = kI8StageK + 16;  // padded LDS row: 20 dwords, conflict-free 16-byte accesses
+constexpr int kI8StageBytes = (kI8Rows + kI8Tokens) * kI8RowBytes;
+constexpr int kI8OutRow = kI8Rows * 2 + 16;  // bytes per token of the fp16 output tile in LDS
+constexpr int kI8LdsBytes = 2 * kI8StageBytes > kI8Tokens * kI8OutRow ? 2 * kI8StageBytes : kI8Tokens * kI8OutRow;
+
+__device__ __forceinline__ rsrc_t rsrc_of(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+// ---------------------------------------------------------------------------------------------
+// activation quantizer: one workgroup per token
+
+// byte position p of a 32-column group holds column sigma(p) (see above)
+__host__ __device__ constexpr int sigma(int p) { return 8 * (p & 3) + 4 * ((p >> 2) & 1) + (p >> 3); }
+
+struct ActI8Layout {
+    size_t q_bytes;     // int8 [N][K], every 32-column group permuted
+    size_t absmax_off;  // float [N]
+    size_t sum_off;     // int32 [N]
+    size_t total;
+};
+static ActI8Layout act_i8_layout(int N, int K) {
+    ActI8Layout l;
+    l.q_bytes = ((size_t)N * K + 255) / 256 * 256;
+    l.absmax_off = l.q_bytes;
+    l.sum_off = l.absmax_off + (((size_t)N * 4 + 255) / 256 * 256);
+    l.total = l.sum_off + (((size_t)N * 4 + 255) / 256 * 256);
+    return l;
+}
+size_t act_i8_bytes(int N, int K) { return act_i8_layout(N, K).total; }
+
+__global__ void __launch_bounds__(256) quantize_act_i8_kernel(const uint16_t* __restrict__ x, int K, int8_t* __restrict__ q,
+                                                              float* __restrict__ absmax, int32_t* __restrict__ sums) {
+    __shared__ unsigned wave_max[4];
+    __shared__ int wave_sum[4];
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const uint16_t* xb = x + (size_t)n * K;
+    unsigned mx = 0;  // magnitudes compare like their bit patterns
+    for (int k = tid; k < K; k += 256) mx = max(mx, (unsigned)(xb[k] & 0x7fffu));
+    for (int d = 1; d < 64; d <<= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, d, 64));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = mx;
+    __syncthreads();
+    mx = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    const float amax = (float)__builtin_bit_cast(_Float16, (uint16_t)mx);
+    // the decision is taken in binary32: one correctly rounded division, one product, round to nearest even
+    const float inv = amax > 0.f ? __fdiv_rn(127.0f, amax) : 0.f;
+    int s = 0;
+    for (int g = tid; g < K / 32; g += 256) {
+        int v[32];
+#pragma unroll
+        for (int c = 0; c < 32; ++c) {
+            v[c] = (int)rintf(__fmul_rn((float)__builtin_bit_cast(_Float16, xb[g * 32 + c]), inv));
+            s += v[c];
+        }
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            w[i] = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) w[i] |= (uint32_t)(v[sigma(4 * i + b)] & 0xff) << (8 * b);
+        }
+        uint32_t* dst = reinterpret_cast<uint32_t*>(q + (size_t)n * K + (size_t)g * 32);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dst[i] = w[i];
+    }
+    for (int d = 1; d < 64; d <<= 1) s += __shfl_xor(s, d, 64);
+    if ((tid & 63) == 0) wave_sum[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) {
+        absmax[n] = amax;
+        sums[n] = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+    }
+}
+
+int launch_quantize_act_i8(const void* x, int N, int K, void* out, hipStream_t st) {
+    const ActI8Layout l = act_i8_layout(N, K);
+    uint8_t* o = static_cast<uint8_t*>(out);
+    hipLaunchKernelGGL(quantize_act_i8_kernel, dim3((unsigned)N), dim3(256), 0, st, static_cast<const uint16_t*>(x), K,
+                       reinterpret_cast<int8_t*>(o), reinterpret_cast<float*>(o + l.absmax_off),
+                       reinterpret_cast<int32_t*>(o + l.sum_off));
+    return launch_status();
+}
+
+// ---------------------------------------------------------------------------------------------
+// the product
+
+struct GemmI8Args {
+    const uint8_t* tiles;
+    const int8_t* xq;
+    const float* absmax;
+    const int32_t* sums;
+    _Float16* y;
+    int32_t* acc_out;  // optional: the integer accumulators [N][M]
+    int M, N, K, n_row_blocks, n_ktiles;
+    int m_tiles, n_tiles;
+    int* status;
+};
+
+// The codes of one 32-weight block as 32 bytes in sigma order.
+template <int B>
+__device__ __forceinline__ void codes_to_bytes(const uint32_t (&plane)[B], u32x4& lo, u32x4& hi) {
+    uint32_t codes[4];
+    planes_to_codes<B>(plane, codes);
+    constexpr uint32_t kMask = ((1u << B) - 1u) * 0x01010101u;
+    // word o: even nibbles -> bytes 8 o .. 8 o + 3, odd nibbles -> bytes 8 o + 4 .. 8 o + 7
+    lo = u32x4{codes[0] & kMask, (codes[0] >> 4) & kMask, codes[1] & kMask, (codes[1] >> 4) & kMask};
+    hi = u32x4{codes[2] & kMask, (codes[2] >> 4) & kMask, codes[3] & kMask, (codes[3] >> 4) & kMask};
+}
+
+template <int B, int GQ, bool HZ>
+__global__ void __launch_bounds__(256) mpgemm_i8_kernel(GemmI8Args a) {
+    constexpr int MSZ = HZ ? 4 : 2;
+    constexpr int MPL = (kKTile / GQ) * MSZ;
+    constexpr int TB = B * 1024 + 64 * MPL;
+    constexpr int CH = kKTile / B;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    __shared__ float row_scale[kI8Rows], row_zs[kI8Rows];  // scale[m] and zero[m] * scale[m]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int mt = blockIdx.x / a.n_tiles, nt = blockIdx.x % a.n_tiles;
+    // a blob packed for another shape or layout: say so and leave y alone (one exit)
+    const bool header_ok = header_matches(a.tiles, a.M, a.K, B, GQ, HZ ? 1 : 0);
+    if (!header_ok && blockIdx.x == 0 && tid == 0) report_header_mismatch(a.status);
+    if (mt >= (header_ok ? a.m_tiles : 0)) return;
+    const int n0 = nt * kI8Tokens;
+    const int k_stages = (a.K + kI8StageK - 1) / kI8StageK;  // K is a multiple of 32; a last half stage reads zeros
+
+    // roles in the weight transposition: wave w -> row block w / 2 of the tile, 32-weight block w % 2 of the stage
+    const int wrb = mt * 2 + (wave >> 1), wblk = wave & 1;
+    const bool wvalid = wrb < a.n_row_blocks;
+    const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? wrb : 0) * a.n_ktiles * TB;
+    const uint32_t wbytes = wvalid ? (uint32_t)(a.n_ktiles * TB) : 0u;
+    const int k32_total = a.K / 32;
+    auto load_planes = [&](uint32_t (&plane)[B], int stage) {
+        const int k32 = stage * 2 + wblk;  // 32-weight block along K
+        const rsrc_t rw = rsrc_of(wsrc, k32 < k32_total ? wbytes : 0u);
+        const int tile = k32 >> 2, kb32 = k32 & 3;
+        const int v = (kb32 * 32) / CH, ksub = ((kb32 * 32) % CH) / 32;
+        const int so = tile * TB + v * 1024 + ksub * B * 4;
+        if constexpr (B == 4) {
+            const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rw, lane * 16, so, 0);
+            plane[0] = w.x; plane[1] = w.y; plane[2] = w.z; plane[3] = w.w;
+        } else if constexpr (B == 2) {
+            const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rw, lane * 16, so, 0);
+            plane[0] = w.x; plane[1] = w.y;
+        } else {
+            plane[0] = __builtin_amdgcn_raw_buffer_load_b32(rw, lane * 16, so, 0);
+        }
+    };
+    // activations of a stage: thread -> token tid / 2, 32 bytes at column half tid % 2; tokens beyond N and columns
+    // beyond K lie outside the resource and read as zero
+    const int xtok = tid >> 1, xhalf = tid & 1;
+    const rsrc_t rx = rsrc_of(a.xq, (uint32_t)a.N * (uint32_t)a.K);
+    auto load_x = [&](u32x4 (&xv)[2], int stage) {
+        const int col = stage * kI8StageK + xhalf * 32;
+        const bool in = (n0 + xtok) < a.N && col < a.K;
+        const uint32_t off = in ? (uint32_t)(n0 + xtok) * (uint32_t)a.K + (uint32_t)col : 0xFFFFFFF0u;
+        xv[0] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+        xv[1] = __builtin_amdgcn_raw_buffer_load_b128(rx, in ? off + 16u : 0xFFFFFFF0u, 0, 0);
+    };
+
+    i32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+    const int wm = wave >> 1, wn = wave & 1, r = lane & 31, h = lane >> 5;
+
+    uint32_t plane[B];
+    u32x4 xv[2];
+    load_planes(plane, 0);
+    load_x(xv, 0);
+    // scale and zero of the tile's rows (the first quantization block of a row stands for the whole row)
+    if (tid < kI8Rows) {
+        const int rb = mt * 2 + (tid >> 6), l = tid & 63;
+        float sc = 0.f, zs = 0.f;
+        if (rb < a.n_row_blocks) {
+            const uint8_t* meta = a.tiles + (size_t)rb * a.n_ktiles * TB + B * 1024 + l * MPL;
+            sc = (float)*reinterpret_cast<const _Float16*>(meta);
+            zs = HZ ? (float)*reinterpret_cast<const _Float16*>(meta + 2) * sc : 0.f;
+        }
+        row_scale[tid] = sc;
+        row_zs[tid] = zs;
+    }
+    for (int s = 0; s < k_stages; ++s) {
+        uint8_t* buf = smem + (s & 1) * kI8StageBytes;
+        {
+            u32x4 lo, hi;
+            codes_to_bytes<B>(plane, lo, hi);
+            uint8_t* wrow = buf + ((wave >> 1) * 64 + lane) * kI8RowBytes + wblk * 32;
+            *reinterpret_cast<u32x4*>(wrow) = lo;
+            *reinterpret_cast<u32x4*>(wrow + 16) = hi;
+            uint8_t* xrow = buf + (kI8Rows + xtok) * kI8RowBytes + xhalf * 32;
+            *reinterpret_cast<u32x4*>(xrow) = xv[0];
+            *reinterpret_cast<u32x4*>(xrow + 16) = xv[1];
+        }
+        if (s + 1 < k_stages) {
+            load_planes(plane, s + 1);
+            load_x(xv, s + 1);
+        }
+        __syncthreads();
+        const uint8_t* wbase = buf + (wm * 64 + r) * kI8RowBytes + h * 16;
+        const uint8_t* xbase = buf + (kI8Rows + wn * 64 + r) * kI8RowBytes + h * 16;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            i32x4 wf[2], xf[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                wf[i] = *reinterpret_cast<const i32x4*>(wbase + i * 32 * kI8RowBytes + ks * 32);
+                xf[i] = *reinterpret_cast<const i32x4*>(xbase + i * 32 * kI8RowBytes + ks * 32);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[i], xf[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();  // every wave is done with the stage buffers, which the output tile reuses
+
+    // epilogue: C[i][j] of a 32 x 32 tile: i = row 8 (v / 4) + 4 h + v % 4, j = token lane % 32
+    uint8_t* otile = smem;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int tok = wn * 64 + j * 32 + r, gn = n0 + tok;
+        const bool live = gn < a.N;
+        const float delta = live ? a.absmax[gn] * (1.0f / 127.0f) : 0.f;
+        const float sx = live ? (float)a.sums[gn] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int row = wm * 64 + i * 32 + 8 * g4 + 4 * h;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float av = (float)acc[i][j][4 * g4 + e];
+                    // (c - z) s summed: s acc - (z s) sum(xq); sign form (2 c - 1) s: 2 s acc - s sum(xq)
+                    v[e] = HZ ? delta * fmaf(row_scale[row + e], av, -row_zs[row + e] * sx)
+                              : delta * row_scale[row + e] * fmaf(2.f, av, -sx);
+                }
+                half2_t p0, p1;
+                p0.x = (_Float16)v[0]; p0.y = (_Float16)v[1];
+                p1.x = (_Float16)v[2]; p1.y = (_Float16)v[3];
+                u32x2 w = {__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1)};
+                *reinterpret_cast<u32x2*>(otile + tok * kI8OutRow + row * 2) = w;
+                if (a.acc_out && live) {
+                    const int gm = mt * kI8Rows + row;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (gm + e < a.M) a.acc_out[(size_t)gn * a.M + gm + e] = acc[i][j][4 * g4 + e];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int m0 = mt * kI8Rows;
+    const bool fast = (a.M % 8 == 0);  // 16-byte aligned rows of y
+    for (int piece = tid; piece < kI8Tokens * (kI8Rows / 8); piece += 256) {
+        const int n = piece / (kI8Rows / 8), c8 = piece % (kI8Rows / 8);
+        const int gn = n0 + n, gm = m0 + c8 * 8;
+        if (gn >= a.N || gm >= a.M) continue;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(otile + n * kI8OutRow + c8 * 16);
+        _Float16* dst = a.y + (size_t)gn * a.M + gm;
+        if (fast && gm + 8 <= a.M) {
+            *reinterpret_cast<u32x4*>(dst) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            for (int t = 0; t < 8 && gm + t < a.M; ++t)
+                dst[t] = __builtin_bit_cast(_Float16, (uint16_t)(w[t >> 1] >> (16 * (t & 1))));
+        }
+    }
+}
+
+template <int B, int GQ, bool HZ>
+static int launch_i8_cfg(GemmI8Args a, hipStream_t st) {
+    static std::once_flag once;
+    static hipError_t attr_rc = hipSuccess;
+    std::call_once(once, [] {
+        attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&mpgemm_i8_kernel<B, GQ, HZ>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, kI8LdsBytes);
+    });
+    if (attr_rc != hipSuccess) return TMAN_ERR_LAUNCH;
+    a.m_tiles = (a.n_row_blocks + 1) / 2;
+    a.n_tiles = (a.N + kI8Tokens - 1) / kI8Tokens;
+    hipLaunchKernelGGL((mpgemm_i8_kernel<B, GQ, HZ>), dim3((unsigned)(a.m_tiles * a.n_tiles)), dim3(256), kI8LdsBytes, st, a);
+    return launch_status();
+}
+
+template <int B, bool HZ>
+static int launch_i8_group(int group, const GemmI8Args& a, hipStream_t st) {
+    switch (group) {
+        case 32: return launch_i8_cfg<B, 32, HZ>(a, st);
+        case 64: return launch_i8_cfg<B, 64, HZ>(a, st);
+        default: return launch_i8_cfg<B, 128, HZ>(a, st);
+    }
+}
+
+int launch_mpgemm_i8(const Layout& L, const void* packed, const void* xq_buf, int N, void* y, void* acc_out, hipStream_t st) {
+    const ActI8Layout al = act_i8_layout(N, L.K);
+    const uint8_t* xb = static_cast<const uint8_t*>(xq_buf);
+    GemmI8Args a;
+    a.tiles = static_cast<const uint8_t*>(packed) + kHeaderBytes;
+    a.xq = reinterpret_cast<const int8_t*>(xb);
+    a.absmax = reinterpret_cast<const float*>(xb + al.absmax_off);
+    a.sums = reinterpret_cast<const int32_t*>(xb + al.sum_off);
+    a.y = static_cast<_Float16*>(y);
+    a.acc_out = static_cast<int32_t*>(acc_out);
+    a.M = L.M;
+    a.N = N;
+    a.K = L.K;
+    a.n_row_blocks = L.n_row_blocks;
+    a.n_ktiles = L.n_ktiles;
+    a.m_tiles = a.n_tiles = 0;
+    a.status = device_status_word();
+    if (!a.status) return TMAN_ERR_LAUNCH;
+    if (L.bits == 1) return L.has_zero ? launch_i8_group<1, true>(L.group, a, st) : launch_i8_group<1, false>(L.group, a, st);
+    if (L.bits == 2) return launch_i8_group<2, true>(L.group, a, st);
+    return launch_i8_group<4, true>(L.group, a, st);
+}
+
+}  // namespace tman
