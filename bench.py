@@ -30,6 +30,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 MFMA_F16_PEAK_TFLOPS = 2500.0
+MFMA_I8_PEAK_TOPS = 5000.0
 
 # HBM bytes per launch of the dominant kernels on the default workloads, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script scaled by a plain copy of known size (--calibration-copy); the counters
@@ -295,6 +296,42 @@ def other_configs(args, torch, tman, synth, oracle, dev):
         err, rows = prefill_error(oracle, q, sc, z, xh, py, pw)
         add(f"{pw.name}: {spec.M}x{spec.K} uint4 g64, N={NP}", sec, tf, "TFLOP/s", MFMA_F16_PEAK_TFLOPS, err,
             f"{len(rows)} whole tokens (first, last, tile edges, seeded picks)")
+    # per-tensor / per-channel formats on the integer matrix cores (Sec. 6.1 BitNet shapes; the prefill shape for scale)
+    for (M, K, bits, label) in ((6912, 2560, 2, "BitNet-2B-style 6912x2560, ternary weights as 2-bit codes, one scale per tensor"),
+                                (2560, 6912, 2, "BitNet-2B-style 2560x6912, ternary weights as 2-bit codes, one scale per tensor"),
+                                (11008, 4096, 4, "11008x4096 uint4, one scale and zero per row")):
+        NP, group = 1024, 64
+        seed = 0x18000 + M
+        q = synth.uniform_codes(seed, M * K, bits).reshape(M, K)
+        if bits == 2:
+            q = (q % 3).astype(np.uint8)
+            rs, rz = np.full(M, np.float16(0.037)), np.ones(M, dtype=np.float16)
+        else:
+            rs, rz = synth.uniform_fp16(seed + 1, M, 0.005, 0.02), synth.uniform_fp16(seed + 2, M, 6.0, 9.0)
+        xh = synth.normal_fp16(seed + 3, NP * K).reshape(NP, K)
+        sh = tman.Shape(M, K, bits, group, True)
+        blob = torch.empty(tman.tman_packed_bytes(sh), dtype=torch.uint8, device=dev)
+        tman.tman_pack_weights(sh, torch.from_numpy(q).to(dev), torch.from_numpy(np.repeat(rs.reshape(M, 1), K // group, 1)).to(dev),
+                               torch.from_numpy(np.repeat(rz.reshape(M, 1), K // group, 1)).to(dev), blob)
+        px = torch.from_numpy(xh).to(dev)
+        xq = torch.empty(tman.tman_act_i8_bytes(NP, K), dtype=torch.uint8, device=dev)
+        py = torch.empty((NP, M), dtype=torch.float16, device=dev)
+        tman.tman_quantize_act_i8(px, NP, K, xq)
+        sec = timed_steps(torch, lambda i: tman.tman_mpgemm_i8(sh, blob, xq, NP, py, None), 40, 100)
+
+        def both(i):
+            tman.tman_quantize_act_i8(px, NP, K, xq)
+            tman.tman_mpgemm_i8(sh, blob, xq, NP, py, None)
+
+        sec_both = timed_steps(torch, both, 20, 100)
+        rows = [0, 1, 127, 128, NP // 2, NP - 1] + np.random.default_rng(M).integers(0, NP, 10).tolist()
+        xo, mo = oracle.quantize_activations_i8(xh[rows])
+        _, Y = oracle.matmul_i8(q, rs, rz, xo, mo, bits)
+        err = float(oracle.row_relative_error(py[rows].cpu().numpy().astype(np.float64), Y).max())
+        tops = 2.0 * NP * M * K / sec / 1e12
+        add(f"int8 matrix cores: {label}, N={NP} (tman_mpgemm_i8 alone; with the activation quantizer launch "
+            f"{sec_both * 1e6:.1f} us); error against the oracle for the integer activations, bound 1e-3",
+            sec, tops, "TOP/s", MFMA_I8_PEAK_TOPS, err, f"{len(rows)} whole tokens")
     return out
 
 
