@@ -293,6 +293,39 @@ int tman_noalloc_init(void);
 int tman_mpgemv_noalloc(const tman_shape_t *shape, const void *packed, const void *lut, int32_t N, void *y,
                         void *stream);
 
+/*
+ * The tiling (Sec. 4.1 "Unified tiling strategy", Eq. 1-4: tile sizes searched per machine under register /
+ * on-chip-memory constraints, the prefill and the decoding loop nest covering the same M and K extents of the one
+ * weight copy).  The shared tile block is fixed by the packed layout (64 rows x 128 columns, which is Eq. 2 and
+ * Eq. 3 by construction); free is how many tile blocks one workgroup takes:
+ *   decode_seg_tiles / _many   K tiles per workgroup of tman_mpgemv for 1-2 / 4-8 tokens
+ *   decode_x_seg_tiles         tman_mpgemv_x: a K of at most this many tiles, and at most decode_x_whole_bytes of
+ *                              packed weights per row block, is ONE segment; it is at most 32 (Eq. 1: the tables
+ *                              of a segment, 1 KB per tile, live in the workgroup's 32 KB of LDS)
+ *   decode_x_long_seg_tiles    ... a longer K is cut into equal segments of at most this many tiles
+ *   small_seg_tiles            K tiles per workgroup of tman_mpgemm for N <= 32
+ *   prefill_row_blocks         tile blocks in M per workgroup of the tiled prefill kernel, 1..4 (Eq. 4: four
+ *                              stage buffers of rows x 80 + 256 x 64 bytes within 160 KB of LDS), 0 = chosen per
+ *                              call from the grid it gives
+ * tman_default_tiling gives the built-in values (the best of the measured sweep paper_2511_11248_amd/tune.py
+ * makes on the device), tman_get_tiling the current ones; tman_set_tiling checks the constraints
+ * (TMAN_ERR_SHAPE if violated) and makes the values current for all later calls of the process.  The tiling
+ * enters the workspace size queries and the descriptor tables: set it before sizing workspaces and preparing
+ * batches, not between a prepare and its runs.
+ */
+typedef struct tman_tiling {
+    int32_t decode_seg_tiles;
+    int32_t decode_seg_tiles_many;
+    int32_t decode_x_seg_tiles;
+    int32_t decode_x_long_seg_tiles;
+    int32_t decode_x_whole_bytes;
+    int32_t small_seg_tiles;
+    int32_t prefill_row_blocks;
+} tman_tiling_t;
+int tman_default_tiling(tman_tiling_t *out);
+int tman_get_tiling(tman_tiling_t *out);
+int tman_set_tiling(const tman_tiling_t *tiling);
+
 /* Static, human-readable name of a status code. */
 const char *tman_status_string(int status);
 

@@ -25,6 +25,16 @@ class TmanError(RuntimeError):
         super().__init__(f"{where}: {tman_status_string(status)} (status {status})")
 
 
+class Tiling(C.Structure):
+    """Mirror of ``tman_tiling_t`` (see include/tman.h)."""
+    _fields_ = [("decode_seg_tiles", C.c_int32), ("decode_seg_tiles_many", C.c_int32), ("decode_x_seg_tiles", C.c_int32),
+                ("decode_x_long_seg_tiles", C.c_int32), ("decode_x_whole_bytes", C.c_int32), ("small_seg_tiles", C.c_int32),
+                ("prefill_row_blocks", C.c_int32)]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
 class _CShape(C.Structure):
     _fields_ = [("M", C.c_int32), ("K", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32), ("flags", C.c_int32)]
 
@@ -118,6 +128,9 @@ def _load():
         L.tman_noalloc_init.argtypes = []
         L.tman_mpgemv_noalloc.restype = C.c_int
         L.tman_mpgemv_noalloc.argtypes = [sp, vp, vp, C.c_int32, vp, vp]
+        for fn in (L.tman_default_tiling, L.tman_get_tiling, L.tman_set_tiling):
+            fn.restype = C.c_int
+            fn.argtypes = [C.POINTER(Tiling)]
         L.tman_status_string.restype = C.c_char_p
         L.tman_status_string.argtypes = [C.c_int]
         L.tman_layout_version.restype = C.c_int32
@@ -241,6 +254,22 @@ def tman_check_packed(shape: Shape, packed, stream=None) -> int:
 def tman_device_status(stream=None) -> int:
     """Returns and clears the device status word (0, or -8 when a kernel met a blob with a foreign header)."""
     return int(_load().tman_device_status(_stream(stream)))
+
+
+def tman_default_tiling() -> Tiling:
+    t = Tiling()
+    _check(_load().tman_default_tiling(C.byref(t)), "tman_default_tiling")
+    return t
+
+
+def tman_get_tiling() -> Tiling:
+    t = Tiling()
+    _check(_load().tman_get_tiling(C.byref(t)), "tman_get_tiling")
+    return t
+
+
+def tman_set_tiling(t: Tiling) -> None:
+    _check(_load().tman_set_tiling(C.byref(t)), "tman_set_tiling")
 
 
 def tman_noalloc_init() -> None:

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtman.so")
 
-SOURCES = ["tman_abi.hip", "tman_pack.hip", "tman_lut.hip", "tman_mpgemv.hip", "tman_mpgemv_i16.hip", "tman_mpgemv_x.hip", "tman_mpgemm.hip", "tman_mpgemm_small.hip", "tman_mpgemm_i8.hip", "tman_noalloc.hip"]
+SOURCES = ["tman_abi.hip", "tman_tiling.hip", "tman_pack.hip", "tman_lut.hip", "tman_mpgemv.hip", "tman_mpgemv_i16.hip", "tman_mpgemv_x.hip", "tman_mpgemm.hip", "tman_mpgemm_small.hip", "tman_mpgemm_i8.hip", "tman_noalloc.hip"]
 
 # -packed-fp32-ops: keep the compiler from forming packed fp32 VALU instructions
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -79,8 +79,11 @@ __device__ __forceinline__ void report_header_mismatch(int* status) {
 
 // Decode scheduling: a workgroup (four waves) owns one row block and one K segment of at most this
 // many tiles; longer K is cut into equal segments that meet through the workspace.
-constexpr int kGemvSegmentTiles = 32;
-constexpr int kGemvManyTokensSegmentTiles = 24;  // for 4 or 8 tokens
+// The tile counts below are the library's tiling (Sec. 4.1 "Unified tiling strategy"): defaults found by the
+// measured search in paper_2511_11248_amd/tune.py, replaceable at run time with tman_set_tiling (which checks the
+// constraints that play the part of Eq. 1-4 on this machine).
+constexpr int kGemvXSegmentTiles = 32;  // tables one workgroup of the one-token kernel can hold (32 KB of LDS)
+tman_tiling_t current_tiling();
 
 // One GEMV of a decode launch, as the kernel sees it.
 struct GemvDesc {
@@ -107,8 +110,6 @@ GemvPlan plan_gemv(const Layout& L, int N);
 GemvPlan plan_segments(const Layout& L, int np, int max_seg);
 // Plan of the one-token kernel that builds its tables itself: at most 32 tiles per segment (32 KB of tables
 // in LDS), 24 when K has to be cut anyway.
-constexpr int kGemvXSegmentTiles = 32;
-constexpr int kGemvXLongSegmentTiles = 24;
 GemvPlan plan_gemv_x(const Layout& L);
 void fill_desc_plan(GemvDesc& d, const Layout& L, const GemvPlan& p, const void* packed, const void* lut, int N, void* y,
                     void* workspace, int wg_begin);

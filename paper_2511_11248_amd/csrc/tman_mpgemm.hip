@@ -461,6 +461,8 @@ static int choose_row_blocks(int n_row_blocks, int N) {
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
             n_cu = n;
     });
+    const int forced = current_tiling().prefill_row_blocks;
+    if (forced >= 1 && forced <= 4) return forced;
     const int n_tiles = (N + kTN - 1) / kTN;
     // A grid that leaves compute units idle even with one row block per workgroup: the time of a workgroup
     // is then set by the chain load -> dequantize -> barrier of its stages, shortest with the smallest tile.

@@ -35,7 +35,7 @@ constexpr int kRedStride = kRows + 4;                  // floats per token in th
 
 GemvPlan plan_small(const Layout& L) {
     // a dequantized tile takes about as long as a looked-up tile of one token: the same segment lengths
-    GemvPlan p = plan_segments(L, 1, kGemvSegmentTiles);
+    GemvPlan p = plan_segments(L, 1, current_tiling().small_seg_tiles);
     p.np = kSmallTokens;
     p.partial_bytes = p.n_seg > 1 ? (size_t)L.n_row_blocks * p.n_seg * kSmallTokens * kRows * sizeof(float) : 0;
     return p;

@@ -50,7 +50,8 @@ GemvPlan plan_segments(const Layout& L, int np, int max_seg) {
 GemvPlan plan_gemv(const Layout& L, int N) {
     const int np = padded_tokens(N);
     // with four or eight tokens a tile takes about twice as long: shorter segments, more workgroups (measured)
-    return plan_segments(L, np, np >= 4 ? kGemvManyTokensSegmentTiles : kGemvSegmentTiles);
+    const tman_tiling_t t = current_tiling();
+    return plan_segments(L, np, np >= 4 ? t.decode_seg_tiles_many : t.decode_seg_tiles);
 }
 
 void fill_desc_plan(GemvDesc& d, const Layout& L, const GemvPlan& p, const void* packed, const void* lut, int N,

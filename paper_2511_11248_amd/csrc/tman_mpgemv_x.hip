@@ -23,9 +23,11 @@ namespace tman {
 // workgroup can take whole - up to 32 tiles and about 80 KB of packed weights per row block - is one segment,
 // which spares the exchange of partial sums; a longer K is cut into segments of at most 24 tiles.
 GemvPlan plan_gemv_x(const Layout& L) {
-    int whole = 81920 / L.tile_bytes;
-    if (whole > kGemvXSegmentTiles) whole = kGemvXSegmentTiles;
-    return plan_segments(L, 1, L.n_ktiles <= whole ? whole : kGemvXLongSegmentTiles);
+    const tman_tiling_t t = current_tiling();
+    int whole = t.decode_x_whole_bytes / L.tile_bytes;
+    if (whole > t.decode_x_seg_tiles) whole = t.decode_x_seg_tiles;
+    if (whole < 1) whole = 1;
+    return plan_segments(L, 1, L.n_ktiles <= whole ? whole : t.decode_x_long_seg_tiles);
 }
 
 void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x, void* y, void* workspace) {

@@ -1,0 +1,77 @@
+// The library's tiling and the constraints it must satisfy (Sec. 4.1 "Unified tiling strategy", Eq. 1-4).
+//
+// In the paper a search picks, per machine, the tile sizes of the prefill and of the decoding loop nest under
+// four constraints -- the tables of a decoding tile fit the vector registers (Eq. 1), both loop nests cover the
+// same M extent (Eq. 2) and the same K extent (Eq. 3) of the one pre-permuted weight copy, and the pipeline's
+// stage buffers fit the on-chip memory (Eq. 4) -- and three heuristics (largest K per table set, ...).  Here the
+// shared tile block is fixed by the packed layout: 64 rows x 128 columns for both kernels, which is Eq. 2 and
+// Eq. 3 by construction (a prefill workgroup covers 1..4 tile blocks in M and walks K in four 32-column stages
+// per tile block; a decoding wave covers one tile block in M and the 32 tables of its 128 columns).  What
+// remains free, and what tman_set_tiling can change, is how many tile blocks one workgroup takes:
+//   decode_*            K tiles per decoding workgroup (its K segment); the one-token kernel keeps the tables of
+//                       its whole segment in LDS, so there the segment is bounded like K_lut in Eq. 1:
+//                       seg_tiles x 1 KB of tables <= the 32 KB a workgroup requests;
+//   prefill_row_blocks  tile blocks in M per prefill workgroup; Eq. 4 reads ring (4) x stage bytes <= 160 KB of
+//                       LDS, which admits at most 4.
+// The defaults are the best of the measured sweep in paper_2511_11248_amd/tune.py over the benchmark shapes.
+#include <atomic>
+#include <mutex>
+
+#include "tman_internal.h"
+
+namespace tman {
+
+static constexpr tman_tiling_t kDefaultTiling = {32, 24, 32, 24, 81920, 43, 0};
+static std::mutex tiling_mutex;
+static tman_tiling_t tiling_now = kDefaultTiling;
+
+tman_tiling_t current_tiling() {
+    std::lock_guard<std::mutex> lock(tiling_mutex);
+    return tiling_now;
+}
+
+// Eq. 1 and Eq. 4 in this machine's terms (Eq. 2 and Eq. 3 hold for every value: the tile block is shared).
+static int check_tiling(const tman_tiling_t& t) {
+    constexpr int kLdsBytes = 160 * 1024, kRing = 4;
+    if (t.decode_seg_tiles < 1 || t.decode_seg_tiles_many < 1 || t.small_seg_tiles < 1) return TMAN_ERR_SHAPE;
+    if (t.decode_seg_tiles > 4096 || t.decode_seg_tiles_many > 4096 || t.small_seg_tiles > 4096) return TMAN_ERR_SHAPE;
+    // Eq. 1: the tables of a one-token segment (1 KB per tile) must fit the workgroup's 32 KB
+    if (t.decode_x_seg_tiles < 1 || t.decode_x_seg_tiles * kTableBytesPerKTile > kGemvXSegmentTiles * kTableBytesPerKTile)
+        return TMAN_ERR_SHAPE;
+    if (t.decode_x_long_seg_tiles < 1 || t.decode_x_long_seg_tiles > t.decode_x_seg_tiles) return TMAN_ERR_SHAPE;
+    if (t.decode_x_whole_bytes < 1024) return TMAN_ERR_SHAPE;
+    // Eq. 4: stage ring of the prefill kernel: rows x 80 bytes of fp16 weights + 256 tokens x 64 bytes per stage
+    if (t.prefill_row_blocks < 0 || t.prefill_row_blocks > 4) return TMAN_ERR_SHAPE;
+    const int rb = t.prefill_row_blocks ? t.prefill_row_blocks : 4;
+    if (kRing * (rb * kRows * 80 + 256 * 64) > kLdsBytes) return TMAN_ERR_SHAPE;
+    return TMAN_OK;
+}
+
+}  // namespace tman
+
+using namespace tman;
+
+extern "C" {
+
+int tman_get_tiling(tman_tiling_t* out) {
+    if (!out) return TMAN_ERR_NULL;
+    *out = current_tiling();
+    return TMAN_OK;
+}
+
+int tman_default_tiling(tman_tiling_t* out) {
+    if (!out) return TMAN_ERR_NULL;
+    *out = kDefaultTiling;
+    return TMAN_OK;
+}
+
+int tman_set_tiling(const tman_tiling_t* t) {
+    if (!t) return TMAN_ERR_NULL;
+    const int rc = check_tiling(*t);
+    if (rc != TMAN_OK) return rc;
+    std::lock_guard<std::mutex> lock(tiling_mutex);
+    tiling_now = *t;
+    return TMAN_OK;
+}
+
+}  // extern "C"

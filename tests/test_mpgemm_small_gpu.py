@@ -24,7 +24,7 @@ SMALL = [
     (64, 768, 1, 64, False, 8),      # sign plane
     (64, 512, 1, 128, True, 3),      # 1-bit affine
     (64, 256, 2, 32, True, 31),
-    (64, 4608, 4, 64, True, 4),      # two K segments
+    (64, 5632, 4, 64, True, 4),      # 44 K tiles: two segments
     (130, 8320, 4, 128, True, 8),    # three segments, ragged rows
     (100, 11008, 2, 64, True, 16),   # the longest K of the benchmark shapes
     (1, 32, 4, 32, True, 2),         # degenerate: one row, one group
@@ -36,7 +36,7 @@ SMALL = [
 def test_small_shapes(oracle_lib, M, K, bits, group, hz, N):
     q, s, z, x = rand_case(9000 + M + K + bits + N, M, K, N, bits, group, hz)
     shape = tman.Shape(M, K, bits, group, hz)
-    assert (tman.tman_mpgemm_workspace_bytes(shape, N) > 0) == (K > 4096)
+    assert (tman.tman_mpgemm_workspace_bytes(shape, N) > 0) == (K > 43 * 128)  # a K segment is at most 43 tiles
     y = mpgemm(shape, pack(shape, q, s, z), x)
     assert np.all(np.isfinite(y.astype(np.float32)))
     err = oracle.row_relative_error(y, oracle.matmul(q, s, z, x, bits, group))
@@ -62,7 +62,7 @@ def test_unit_vector_tokens_return_dequantized_columns(oracle_lib, bits, group):
 
 
 def test_deterministic_and_workspace_reusable(oracle_lib):
-    M, K, bits, group, N = 512, 11008, 2, 64, 8  # four K segments: exercises the ticketed reduction
+    M, K, bits, group, N = 512, 11008, 2, 64, 8  # two K segments of 43 tiles: exercises the ticketed reduction
     q, s, z, x = rand_case(61, M, K, N, bits, group)
     shape = tman.Shape(M, K, bits, group)
     blob = pack(shape, q, s, z)
@@ -118,7 +118,7 @@ def test_batched_layer_set_full_size(oracle_lib, N):
 
 def test_batch_of_mixed_small_shapes_and_a_foreign_blob(oracle_lib):
     bits, group, N = 2, 64, 6
-    dims = [(70, 192), (64, 4608), (130, 8320), (1, 64), (257, 4096)]
+    dims = [(70, 192), (64, 5632), (130, 8320), (1, 64), (257, 4096)]
     shapes, blobs, xs, ys, wss, refs = [], [], [], [], [], []
     for i, (M, K) in enumerate(dims):
         q, s, z, x = rand_case(950 + i, M, K, N, bits, group)
