@@ -180,6 +180,39 @@ __device__ __forceinline__ float sum_over_lanes(float v) {
     return v;
 }
 
+// One table of the one-token kernels: `xw` holds the table's four fp16 activations; the 16 entries (entry p = sum
+// of the activations whose bit of p is set, added in ascending order, rounded to fp16 once) go to LDS at
+// lt + j * 32, and the sum of every quantization group (TPG consecutive tables, held by TPG consecutive lanes)
+// to ls + (j / TPG) * 4.  All lanes take part in the lane sum; `live` false stores nothing.
+template <int TPG>
+__device__ __forceinline__ void store_table(const u32x2& xw, int j, bool live, uint32_t lt, uint32_t ls) {
+    // (copy the elements out first: a bit cast applied directly to a vector element reads element 0)
+    const uint32_t w01 = xw.x, w23 = xw.y;
+    const half2_t x01 = __builtin_bit_cast(half2_t, w01), x23 = __builtin_bit_cast(half2_t, w23);
+    const float v[4] = {(float)x01[0], (float)x01[1], (float)x23[0], (float)x23[1]};
+    float e[16];
+    e[0] = 0.f;
+    e[1] = v[0];
+    e[2] = v[1];
+    e[3] = v[0] + v[1];
+#pragma unroll
+    for (int p = 4; p < 8; ++p) e[p] = p == 4 ? v[2] : e[p - 4] + v[2];
+#pragma unroll
+    for (int p = 8; p < 16; ++p) e[p] = p == 8 ? v[3] : e[p - 8] + v[3];
+    half8_t lo, hi;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        lo[p] = (_Float16)e[p];
+        hi[p] = (_Float16)e[p + 8];
+    }
+    const float gs = sum_over_lanes<TPG>((v[0] + v[1]) + (v[2] + v[3]));
+    if (live) {
+        store_lds<u32x4>(lt + j * 32, __builtin_bit_cast(u32x4, lo));
+        store_lds<u32x4>(lt + j * 32 + 16, __builtin_bit_cast(u32x4, hi));
+        if (j % TPG == 0) store_lds<float>(ls + (j / TPG) * 4, gs);
+    }
+}
+
 // Lookups of one tile block; `tbase` is the LDS address of the tile's 32 tables, `sbase` of its group sums.
 template <int B, int GQ, bool HZ>
 __device__ __forceinline__ void consume_weights(const Stage<B, 1, GemvCfg<B, 1, GQ, HZ>::MPL>& s, uint32_t tbase,

@@ -84,54 +84,33 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
     const uint32_t ls = lt + (uint32_t)seg_tiles * kTableBytesPerKTile;  // group sums follow the tables
     const uint32_t lr = ls + (uint32_t)seg_tiles * Cfg::GPT * 4;         // then the partial sums [wave][row]
 
-    // first weight tiles on their way before anything else
+    // The activations are requested first and the first weight tiles right behind them: a wave's loads return in
+    // the order they were issued, so activations queued behind weight tiles (which come from HBM) would hold the
+    // tables back until those tiles are in; this way the tables are built while the weights travel.
+    const uint32_t x_start = (uint32_t)(k0 * kKTile * 2);  // k0 < n_ktiles, so this lies inside x
+    // (the range check of a buffer load covers the per-lane offset only, not the scalar offset, so the resource
+    // starts at the segment's first activation and ends with x: K * 2 bytes less the segment's start)
+    const rsrc_t rx = make_rsrc(uniform(d.lut_t) + x_start, (uint32_t)uniform(d.K) * 2u - x_start);
+    constexpr int kPasses = kGemvXSegmentTiles * kTablesPerKTile / (kWaves * 64);
+    static_assert(kPasses * kWaves * 64 == kGemvXSegmentTiles * kTablesPerKTile, "whole passes");
+    u32x2 xv[kPasses];  // (a pass beyond the segment reads activations nobody uses; x beyond K reads as zero)
+#pragma unroll
+    for (int i = 0; i < kPasses; ++i)
+        xv[i] = __builtin_amdgcn_raw_buffer_load_b64(rx, (i * kWaves * 64 + tid) * 8, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     Stage<B, 1, Cfg::MPL> st[D] = {};
 #pragma unroll
     for (int s = 0; s < D; ++s) issue_weights<B, 1, GQ, HZ>(st[s], src, t0 + s < t1, t0 + s, lane);
+    __builtin_amdgcn_sched_barrier(0);
 
-    // tables and group sums of the segment: thread -> tables tid, tid + 256, ... (x beyond K reads as zero).
-    // The range check of a buffer load covers the per-lane offset only, not the scalar offset, so the resource
-    // starts at the segment's first activation and ends with x: K * 2 bytes less the segment's start.
+    // tables and group sums of the segment: thread -> tables tid, tid + 256, ...
     {
-        const uint32_t x_start = (uint32_t)(k0 * kKTile * 2);  // k0 < n_ktiles, so this lies inside x
-        const rsrc_t rx = make_rsrc(uniform(d.lut_t) + x_start, (uint32_t)uniform(d.K) * 2u - x_start);
         const int n_tab = (k1 - k0) * kTablesPerKTile;
-        constexpr int kPasses = kGemvXSegmentTiles * kTablesPerKTile / (kWaves * 64);
-        static_assert(kPasses * kWaves * 64 == kGemvXSegmentTiles * kTablesPerKTile, "whole passes");
-        u32x2 xv[kPasses];  // all requests first (a pass beyond the segment reads activations nobody uses)
-#pragma unroll
-        for (int i = 0; i < kPasses; ++i)
-            xv[i] = __builtin_amdgcn_raw_buffer_load_b64(rx, (i * kWaves * 64 + tid) * 8, 0, 0);
 #pragma unroll
         for (int i = 0; i < kPasses; ++i) {
             if (i * kWaves * 64 >= n_tab) break;
             const int j = i * kWaves * 64 + tid;
-            // (copy the elements out first: a bit cast applied directly to a vector element reads element 0)
-            const uint32_t w01 = xv[i].x, w23 = xv[i].y;
-            const half2_t x01 = __builtin_bit_cast(half2_t, w01), x23 = __builtin_bit_cast(half2_t, w23);
-            const float v[4] = {(float)x01[0], (float)x01[1], (float)x23[0], (float)x23[1]};
-            // entry p = sum of the v[t] with bit t of p set, added in ascending t
-            float e[16];
-            e[0] = 0.f;
-            e[1] = v[0];
-            e[2] = v[1];
-            e[3] = v[0] + v[1];
-#pragma unroll
-            for (int p = 4; p < 8; ++p) e[p] = p == 4 ? v[2] : e[p - 4] + v[2];
-#pragma unroll
-            for (int p = 8; p < 16; ++p) e[p] = p == 8 ? v[3] : e[p - 8] + v[3];
-            half8_t lo, hi;
-#pragma unroll
-            for (int p = 0; p < 8; ++p) {
-                lo[p] = (_Float16)e[p];
-                hi[p] = (_Float16)e[p + 8];
-            }
-            const float gs = sum_over_lanes<TPG>((v[0] + v[1]) + (v[2] + v[3]));
-            if (j < n_tab) {
-                store_lds<u32x4>(lt + j * 32, __builtin_bit_cast(u32x4, lo));
-                store_lds<u32x4>(lt + j * 32 + 16, __builtin_bit_cast(u32x4, hi));
-                if (j % TPG == 0) store_lds<float>(ls + (j / TPG) * 4, gs);
-            }
+            store_table<TPG>(xv[i], j, j < n_tab, lt, ls);
         }
     }
     __syncthreads();
@@ -161,8 +140,9 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
     store_lds<float>(lr + (wave * kRows + lane) * 4, y);
     __syncthreads();
     if (wave != 0) return;
-    y = ((load_lds<float>(lr + lane * 4) + load_lds<float>(lr + (kRows + lane) * 4)) +
-         load_lds<float>(lr + (2 * kRows + lane) * 4)) + load_lds<float>(lr + (3 * kRows + lane) * 4);
+    y = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) y += load_lds<float>(lr + (w * kRows + lane) * 4);
     float yy[1] = {y};
     const float one[1] = {1.f};
     finish_rows<1>(d, rb, seg, n_seg, lane, yy, one);
