@@ -65,8 +65,9 @@ struct WRegs {
 // Field f of code word o (weight 4f + o) is turned into an fp16 number without moving it to bit 0:
 // a nibble at mantissa bits 0..3 of 0x6400 reads 1024 + c, one at bits 4..7 reads 1024 + 16c.  Fields
 // f and f + 4 sit 16 bits apart, so one AND-OR makes two such numbers; a single shift by 8 brings
-// fields 2, 3, 6, 7 into reach.  The affine map (c - zero) * scale is then one fp32 FMA per weight
-// with a single rounding to fp16:  (1024 + c) * s - (1024 + z) * s   or   (1024 + 16c) * s/16 - (64 + z) * s.
+// fields 2, 3, 6, 7 into reach.  The affine map (c - zero) * scale is then one fp32 FMA per weight, rounded to
+// fp16 once:  (1024 + c) * s - (1024 + z) * s   or   (1024 + 16c) * s/16 - (64 + z) * s   (the second, constant
+// term is itself rounded to fp32 when the block's constants are prepared).
 // The FMA writes either half of its destination, which puts weights 4f + o and 4f + o + 1 (from the
 // same field of two code words) side by side at no cost.
 template <int B, bool HZ>

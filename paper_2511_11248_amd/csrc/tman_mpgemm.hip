@@ -11,8 +11,11 @@
 //            paper collapses on this hardware to inserting the code into the mantissa of 1024.0
 //            (fp16 0x6400 | c == 1024 + c exactly), and the baked affine table entry
 //            D[c] = fp16((c - zero) * scale) is produced by ONE mixed-precision FMA
-//            fp16( (1024 + c) * scale - (1024 + zero) * scale ) evaluated in fp32 with a single rounding,
-//            with the per-block constants (scale, -(1024 + zero) * scale) computed once per block.
+//            fp16( (1024 + c) * scale - (1024 + zero) * scale ): product and sum are exact inside the FMA
+//            and rounded to fp16 once; the per-block constant -(1024 + zero) * scale, computed once per block,
+//            is rounded to fp32 before (it has up to 24 significant bits), which moves the result by at most
+//            2^-23 * 1040 * scale ahead of that rounding: about 5 % of the entries come out one fp16 step
+//            from fp16((c - zero) * scale).
 //            A lookup per weight in LDS would compete with the MFMA operand reads for LDS bandwidth.
 // The fp16 weight tile goes to LDS and is shared by the waves of the workgroup (each weight is
 // dequantized once per 256 tokens); activations go from global memory straight into LDS.  Pipeline (the
