@@ -84,6 +84,26 @@ def test_full_size_prefill_sampled_tokens(oracle_lib, N):
     assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
 
 
+@pytest.mark.parametrize("N", [256, 1024])
+def test_full_size_prefill_every_token_on_row_bands(oracle_lib, N):
+    """The same launch checked along the other axis: EVERY token of the batch, on three bands of 192 output rows
+    (the first rows, a band across a row-tile edge in the middle, the last rows), so no token tile, wave or lane
+    of the token dimension goes unchecked at full size."""
+    w = synth.WORKLOADS["prefill_w4g64"]
+    spec = w.layers[0]
+    q, s, z = synth.layer_tensors(w, 0, 0)
+    x = synth.activation(w, 0, 0, N)
+    shape = tman.Shape(spec.M, spec.K, w.bits, w.group, True)
+    y = mpgemm(shape, pack(shape, q, s, z), x)
+    rows_per_tile = tman.tman_mpgemm_tile_rows(shape, N)
+    edge = (spec.M // 2) // rows_per_tile * rows_per_tile
+    for lo in (0, edge - 96, spec.M - 192):
+        band = slice(lo, lo + 192)
+        Y = oracle.matmul(q[band], s[band], z[band], x, w.bits, w.group)
+        err = oracle.row_relative_error(y[:, band], Y)
+        assert err.max() <= TOL, f"rows {lo}..{lo + 191}: row-normalised error {err.max():.3e}"
+
+
 @pytest.mark.parametrize("M,rows", [(16384, 64), (32768, 128), (49152, 192), (65536, 256)])
 def test_every_tile_height(oracle_lib, M, rows):
     """Row counts that make the launcher pick each of its four tile heights (the small cases above all run
