@@ -29,7 +29,7 @@ class Tiling(C.Structure):
     """Mirror of ``tman_tiling_t`` (see include/tman.h)."""
     _fields_ = [("decode_seg_tiles", C.c_int32), ("decode_seg_tiles_many", C.c_int32), ("decode_x_seg_tiles", C.c_int32),
                 ("decode_x_long_seg_tiles", C.c_int32), ("decode_x_whole_bytes", C.c_int32), ("small_seg_tiles", C.c_int32),
-                ("prefill_row_blocks", C.c_int32)]
+                ("prefill_row_blocks", C.c_int32), ("decode_x_balance", C.c_int32)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -102,6 +102,9 @@ def _load():
         L.tman_mpgemv_batch_run.argtypes = [C.c_int32, sp, C.c_int32, vp, vp]
         L.tman_mpgemv_x.restype = C.c_int
         L.tman_mpgemv_x.argtypes = [sp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.tman_mpgemv_x_batch_order.restype = C.c_int
+        L.tman_mpgemv_x_batch_order.argtypes = [C.c_int32, sp, C.c_int32, C.POINTER(C.c_uint16), C.c_int32,
+                                                C.POINTER(C.c_int32)]
         L.tman_mpgemv_x_batch_prepare.restype = C.c_int
         L.tman_mpgemv_x_batch_prepare.argtypes = [C.c_int32, sp, vp, vp, vp, vp, vp, vp, vp]
         L.tman_mpgemv_x_batch_run.restype = C.c_int
@@ -364,6 +367,17 @@ def tman_mpgemv_x(shape: Shape, packed, x, y, workspace, stream=None) -> None:
     wb = 0 if workspace is None or isinstance(workspace, int) else _nbytes(workspace)
     _check(_load().tman_mpgemv_x(C.byref(shape.c()), _ptr(packed), _ptr(x), _ptr(y), _ptr(workspace), wb,
                                  _stream(stream)), "tman_mpgemv_x")
+
+
+def tman_mpgemv_x_batch_order(shapes, n_units: int = 0):
+    """The workgroup numbering of a one-token batch as (gemv, workgroup) pairs; empty for a plain grid."""
+    cs = (_CShape * len(shapes))(*[s.c() for s in shapes])
+    n = C.c_int32(0)
+    _check(_load().tman_mpgemv_x_batch_order(len(shapes), cs, n_units, None, 0, C.byref(n)), "tman_mpgemv_x_batch_order")
+    out = (C.c_uint16 * max(1, n.value))()
+    _check(_load().tman_mpgemv_x_batch_order(len(shapes), cs, n_units, out, n.value, C.byref(n)),
+           "tman_mpgemv_x_batch_order")
+    return [(int(out[i]) >> 13, int(out[i]) & 0x1FFF) for i in range(n.value)]
 
 
 def tman_mpgemv_x_batch_prepare(shapes, packed, xs, y, workspace, desc, stream=None) -> None:

@@ -1,6 +1,9 @@
 // C ABI of libtman: argument validation, size queries and dispatch to the kernel launchers.
 // Everything here runs on the host and validates before anything is enqueued.
+#include <cstdlib>
+#include <cstring>
 #include <mutex>
+#include <vector>
 
 #include "tman_internal.h"
 
@@ -163,9 +166,27 @@ int tman_mpgemv(const tman_shape_t* shape, const void* packed, const void* lut, 
     return launch_mpgemv(make_layout(shape), packed, lut, N, y, workspace, (hipStream_t)stream);
 }
 
+// A descriptor table: the GEMV descriptors, then (one-token batches whose workgroups are numbered for balance) the
+// numbering.
+static size_t desc_table_bytes(int count) { return ((size_t)count * sizeof(GemvDesc) + 255) / 256 * 256; }
+static uint16_t* order_of(void* desc, int count) {
+    return reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(desc) + desc_table_bytes(count));
+}
+static int device_units() {
+    static std::once_flag once;
+    static int n_units = 0;
+    std::call_once(once, [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            n_units = n;
+    });
+    return n_units;
+}
+
 size_t tman_mpgemv_batch_desc_bytes(int32_t count) {
     if (count < 1 || count > TMAN_MAX_BATCH) return 0;
-    return (size_t)count * sizeof(GemvDesc);
+    return desc_table_bytes(count) + (size_t)kOrderedMaxWorkgroups * sizeof(uint16_t);
 }
 
 static int check_batch(int32_t count, const tman_shape_t* shapes, int32_t N) {
@@ -264,8 +285,31 @@ int tman_mpgemv_x_batch_prepare(int32_t count, const tman_shape_t* shapes, const
             if (workspace[j] == workspace[i]) return TMAN_ERR_WORKSPACE;  // every GEMV needs its own
         fill_desc_x(host[i], make_layout(&shapes[i]), packed[i], x[i], y[i], workspace[i]);
     }
-    return launch_write_descs(host, count, shapes[0].bits, shapes[0].group, (shapes[0].flags & TMAN_FLAG_HAS_ZERO) ? 1 : 0,
-                              static_cast<GemvDesc*>(desc), (hipStream_t)stream);
+    rc = launch_write_descs(host, count, shapes[0].bits, shapes[0].group, (shapes[0].flags & TMAN_FLAG_HAS_ZERO) ? 1 : 0,
+                            static_cast<GemvDesc*>(desc), (hipStream_t)stream);
+    if (rc != TMAN_OK) return rc;
+    // a launch whose workgroups are all resident at once gets them numbered for equal work per compute unit
+    std::vector<Layout> L(count);
+    for (int i = 0; i < count; ++i) L[i] = make_layout(&shapes[i]);
+    std::vector<uint16_t> order;
+    if (!order_workgroups(count, L.data(), device_units(), &order)) return TMAN_OK;
+    return launch_write_order(order, order_of(desc, count), (hipStream_t)stream);
+}
+
+int tman_mpgemv_x_batch_order(int32_t count, const tman_shape_t* shapes, int32_t n_units, uint16_t* order,
+                              int32_t max_entries, int32_t* n_entries) {
+    int rc = check_batch(count, shapes, 1);
+    if (rc != TMAN_OK) return rc;
+    if (!n_entries) return TMAN_ERR_NULL;
+    if (n_units < 0 || max_entries < 0) return TMAN_ERR_SHAPE;
+    std::vector<Layout> L(count);
+    for (int i = 0; i < count; ++i) L[i] = make_layout(&shapes[i]);
+    std::vector<uint16_t> o;
+    if (!order_workgroups(count, L.data(), n_units > 0 ? n_units : device_units(), &o)) o.clear();
+    *n_entries = (int32_t)o.size();
+    if (order)
+        for (size_t i = 0; i < o.size() && i < (size_t)max_entries; ++i) order[i] = o[i];
+    return TMAN_OK;
 }
 
 int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t* shapes, const void* desc, void* stream) {
@@ -278,6 +322,15 @@ int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t* shapes, const voi
         const GemvPlan p = plan_gemv_x(make_layout(&shapes[i]));
         if (p.n_workgroups > max_wg) max_wg = p.n_workgroups;
         if (p.seg_tiles > max_seg_tiles) max_seg_tiles = p.seg_tiles;
+    }
+    {
+        Layout L[8];
+        for (int i = 0; i < count && i < 8; ++i) L[i] = make_layout(&shapes[i]);
+        if (const int n_wg = ordered_workgroups(count, L, device_units()))
+            return launch_mpgemv_x_ordered(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO,
+                                           static_cast<const GemvDesc*>(desc), count,
+                                           order_of(const_cast<void*>(desc), count), n_wg, max_seg_tiles,
+                                           (hipStream_t)stream);
     }
     return launch_mpgemv_x_batch(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO,
                                  static_cast<const GemvDesc*>(desc), count, max_wg, max_seg_tiles, (hipStream_t)stream);

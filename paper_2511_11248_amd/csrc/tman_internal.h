@@ -1,6 +1,7 @@
 // Internal definitions shared by the HIP translation units of libtman (not part of the public ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <vector>
 #include <stdint.h>
 
 #include "tman.h"
@@ -137,6 +138,12 @@ void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x
 int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y, void* workspace, hipStream_t st);
 int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
                           int max_seg_tiles, hipStream_t st);
+constexpr int kOrderedMaxWorkgroups = 4096;  // room in a descriptor table for a numbering of the workgroups
+int ordered_workgroups(int count, const Layout* L, int n_units);  // workgroups of a numbered launch, 0: plain grid
+bool order_workgroups(int count, const Layout* L, int n_units, std::vector<uint16_t>* order);
+int launch_write_order(const std::vector<uint16_t>& order, uint16_t* dev, hipStream_t st);
+int launch_mpgemv_x_ordered(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv,
+                            const uint16_t* order_dev, int n_wg, int max_seg_tiles, hipStream_t st);
 // a handful of tokens on the matrix cores, scheduled like the decoding kernels (tman_mpgemm with N <= 32, and its batch form)
 GemvPlan plan_small(const Layout& L);
 void fill_desc_small(GemvDesc& d, const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace);

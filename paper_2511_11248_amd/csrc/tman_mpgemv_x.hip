@@ -15,6 +15,9 @@
 //
 // Scheduling is that of mpgemv_kernel: a workgroup of four waves owns one row block and one K segment, the four
 // quarters meet in LDS, segments of a long K meet through the workspace (tickets, fixed order of addition).
+#include <algorithm>
+#include <vector>
+
 #include "tman_gemv_device.h"
 
 namespace tman {
@@ -22,6 +25,11 @@ namespace tman {
 // Segments of the kernel that builds its own tables (measured on the 7B and 3.8B layer sets): a K that one
 // workgroup can take whole - up to 32 tiles and about 80 KB of packed weights per row block - is one segment,
 // which spares the exchange of partial sums; a longer K is cut into segments of at most 24 tiles.
+// LDS of a workgroup whose segment has `seg_tiles` tiles: tables, group sums (at most 4 per tile), partial sums
+static unsigned x_lds_bytes(int seg_tiles) {
+    return (unsigned)seg_tiles * (kTableBytesPerKTile + 4 * 4) + kWaves * kRows * 4;
+}
+
 GemvPlan plan_gemv_x(const Layout& L) {
     const tman_tiling_t t = current_tiling();
     int whole = t.decode_x_whole_bytes / L.tile_bytes;
@@ -35,8 +43,23 @@ void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x
     d.lut_s = nullptr;
 }
 
-template <int B, int GQ, bool HZ, bool SINGLE>
-__global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE> a) {
+// A launch whose workgroups are numbered by the host: workgroup id -> (GEMV, workgroup within the GEMV).  When all
+// workgroups of a launch are resident at once, this chip's dispatcher hands workgroup i to compute unit i mod 256
+// (measured: ids 8, 264, 520, 776 share a unit), so the numbering decides which workgroups share a unit, and the
+// host numbers them so that every unit gets the same amount of work (see order_workgroups).
+struct OrderedArgs {
+    const GemvDesc* descs;
+    const uint16_t* order;  // per workgroup id: GEMV in bits 13..15, workgroup within the GEMV in bits 0..12
+    int n_gemv;
+};
+template <bool SINGLE>
+__device__ __forceinline__ const GemvDesc& desc_of(const OrderedArgs& a, int g) {
+    return a.descs[g];
+}
+
+template <int B, int GQ, bool HZ, bool SINGLE, typename Args>
+__global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(Args a) {
+    constexpr bool ORDERED = __is_same(Args, OrderedArgs);
     using Cfg = GemvCfg<B, 1, GQ, HZ>;
     constexpr int D = Cfg::D;
     constexpr int TPG = GQ / kLutGroup;  // tables per quantization group: 8, 16 or 32 consecutive lanes
@@ -50,10 +73,14 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
 #pragma unroll
     for (int i = 0; i < B; ++i) pw[i] = opaque((float)(1 << i));
 
-    const int g = SINGLE ? 0 : (int)blockIdx.y;
+    int g = SINGLE ? 0 : (int)blockIdx.y, wg_local = (int)blockIdx.x;
+    if constexpr (ORDERED) {
+        const uint32_t e = uniform((int)a.order[blockIdx.x]);
+        g = (int)(e >> 13);
+        wg_local = (int)(e & 0x1fffu);
+    }
     const GemvDesc& d = desc_of<SINGLE>(a, g);
     const int n_seg = uniform(d.n_seg), n_ktiles = uniform(d.n_ktiles);
-    const int wg_local = (int)blockIdx.x;
     // Exits: surplus workgroups of the grid, and (single call) a blob packed for another shape or layout, which is
     // reported and leaves y alone; a batch is checked when its descriptor table is written, which empties the
     // descriptor of such a GEMV.  One exit for both, before any other memory request.
@@ -151,25 +178,20 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(KernelArgs<SINGLE
 // ---------------------------------------------------------------------------------------------
 // launch
 
-// LDS of a workgroup whose segment has `seg_tiles` tiles: tables, group sums (at most 4 per tile), partial sums
-static unsigned x_lds_bytes(int seg_tiles) {
-    return (unsigned)seg_tiles * (kTableBytesPerKTile + 4 * 4) + kWaves * kRows * 4;
-}
-
-template <int B, bool HZ, bool SINGLE>
-static int launch_x_group(int group, const KernelArgs<SINGLE>& a, int n_wg, int max_seg_tiles, hipStream_t st) {
-    const dim3 grid((unsigned)n_wg, (unsigned)a.n_gemv), block(kWaves * 64);
+template <int B, bool HZ, bool SINGLE, typename Args>
+static int launch_x_group(int group, const Args& a, int n_wg, int max_seg_tiles, hipStream_t st) {
+    const dim3 grid((unsigned)n_wg, __is_same(Args, OrderedArgs) ? 1u : (unsigned)a.n_gemv), block(kWaves * 64);
     const unsigned lds = x_lds_bytes(max_seg_tiles);
     switch (group) {
-        case 32: hipLaunchKernelGGL((mpgemv_x_kernel<B, 32, HZ, SINGLE>), grid, block, lds, st, a); break;
-        case 64: hipLaunchKernelGGL((mpgemv_x_kernel<B, 64, HZ, SINGLE>), grid, block, lds, st, a); break;
-        default: hipLaunchKernelGGL((mpgemv_x_kernel<B, 128, HZ, SINGLE>), grid, block, lds, st, a); break;
+        case 32: hipLaunchKernelGGL((mpgemv_x_kernel<B, 32, HZ, SINGLE, Args>), grid, block, lds, st, a); break;
+        case 64: hipLaunchKernelGGL((mpgemv_x_kernel<B, 64, HZ, SINGLE, Args>), grid, block, lds, st, a); break;
+        default: hipLaunchKernelGGL((mpgemv_x_kernel<B, 128, HZ, SINGLE, Args>), grid, block, lds, st, a); break;
     }
     return launch_status();
 }
 
-template <bool SINGLE>
-static int launch_x_format(int bits, int has_zero, int group, const KernelArgs<SINGLE>& a, int n_wg, int max_seg_tiles,
+template <bool SINGLE, typename Args>
+static int launch_x_format(int bits, int has_zero, int group, const Args& a, int n_wg, int max_seg_tiles,
                            hipStream_t st) {
     if (bits == 1) {
         return has_zero ? launch_x_group<1, true, SINGLE>(group, a, n_wg, max_seg_tiles, st)
@@ -187,6 +209,122 @@ int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y,
     if (!a.status) return TMAN_ERR_LAUNCH;
     const GemvPlan p = plan_gemv_x(L);
     return launch_x_format<true>(L.bits, L.has_zero, L.group, a, p.n_workgroups, p.seg_tiles, st);
+}
+
+// Numbers the workgroups of a batch so that, with workgroup i on compute unit i mod n_units, every unit gets the
+// same work: the workgroups, largest first, go one by one to the unit with the least work so far that still has a
+// free place (unit j has a place for ids j, j + n_units, ...), then the two extreme units exchange workgroups
+// while that helps; inside a unit the largest gets the lowest id.  Work of a workgroup = tile blocks of its K
+// segment + 2 (start and end of a workgroup cost about that).  Returns false when the batch does not qualify: more
+// than 8 GEMVs, or more workgroups than are resident at once (LDS of the longest segment, 8 workgroups of four
+// waves per unit at most), in which case the dispatcher no longer goes by position.
+int ordered_workgroups(int count, const Layout* L, int n_units) {
+    if (count > 8 || n_units < 1 || !current_tiling().decode_x_balance) return 0;
+    int n = 0, max_seg_tiles = 0;
+    for (int g = 0; g < count; ++g) {
+        const GemvPlan p = plan_gemv_x(L[g]);
+        if (p.n_workgroups > 0x1fff) return 0;
+        n += p.n_workgroups;
+        max_seg_tiles = std::max(max_seg_tiles, p.seg_tiles);
+    }
+    const int per_unit = std::min(8, (int)(160u * 1024u / x_lds_bytes(max_seg_tiles)));
+    return n <= per_unit * n_units && n <= kOrderedMaxWorkgroups ? n : 0;
+}
+
+bool order_workgroups(int count, const Layout* L, int n_units, std::vector<uint16_t>* order) {
+    if (!ordered_workgroups(count, L, n_units)) return false;
+    struct Item {
+        int cost;
+        uint16_t id;
+    };
+    std::vector<Item> items;
+    for (int g = 0; g < count; ++g) {
+        const GemvPlan p = plan_gemv_x(L[g]);
+        for (int w = 0; w < p.n_workgroups; ++w) {
+            const int seg = w % p.n_seg;
+            const int tiles = std::min(p.seg_tiles, L[g].n_ktiles - seg * p.seg_tiles);
+            items.push_back(Item{tiles + 2, (uint16_t)((g << 13) | w)});
+        }
+    }
+    const int n = (int)items.size();
+    std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.cost > b.cost; });
+    std::vector<int> load(n_units, 0), used(n_units, 0);
+    std::vector<std::vector<uint16_t>> mine(n_units);
+    for (const Item& it : items) {
+        int best = -1;
+        for (int j = 0; j < n_units; ++j) {
+            const int places = n / n_units + (j < n % n_units ? 1 : 0);
+            if (used[j] < places && (best < 0 || load[j] < load[best])) best = j;
+        }
+        load[best] += it.cost;
+        ++used[best];
+        mine[best].push_back(it.id);
+    }
+    // The greedy pass can leave a unit with few places under-filled; even the two extreme units out by exchanging
+    // one workgroup of each while that lowers the larger of their two loads.
+    auto cost_of = [&](uint16_t id) {
+        for (const Item& it : items)
+            if (it.id == id) return it.cost;
+        return 0;
+    };
+    std::vector<std::vector<int>> cost(n_units);
+    for (int j = 0; j < n_units; ++j)
+        for (uint16_t id : mine[j]) cost[j].push_back(cost_of(id));
+    for (int round = 0; round < 4 * n; ++round) {
+        int hi = 0, lo = 0;
+        for (int j = 1; j < n_units; ++j) {
+            if (load[j] > load[hi]) hi = j;
+            if (load[j] < load[lo]) lo = j;
+        }
+        int best_a = -1, best_b = -1, best_max = load[hi];
+        for (size_t a = 0; a < cost[hi].size(); ++a)
+            for (size_t b = 0; b < cost[lo].size(); ++b) {
+                const int d = cost[hi][a] - cost[lo][b];
+                if (d <= 0) continue;
+                const int m = std::max(load[hi] - d, load[lo] + d);
+                if (m < best_max) best_max = m, best_a = (int)a, best_b = (int)b;
+            }
+        if (best_a < 0) break;
+        const int d = cost[hi][best_a] - cost[lo][best_b];
+        std::swap(cost[hi][best_a], cost[lo][best_b]);
+        std::swap(mine[hi][best_a], mine[lo][best_b]);
+        load[hi] -= d;
+        load[lo] += d;
+    }
+    order->assign(n, 0);
+    for (int j = 0; j < n_units; ++j) {
+        std::vector<size_t> by_cost(mine[j].size());
+        for (size_t r = 0; r < by_cost.size(); ++r) by_cost[r] = r;
+        std::stable_sort(by_cost.begin(), by_cost.end(), [&](size_t a, size_t b) { return cost[j][a] > cost[j][b]; });
+        for (size_t r = 0; r < by_cost.size(); ++r) (*order)[r * n_units + j] = mine[j][by_cost[r]];
+    }
+    return true;
+}
+
+int launch_mpgemv_x_ordered(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv,
+                            const uint16_t* order_dev, int n_wg, int max_seg_tiles, hipStream_t st) {
+    OrderedArgs a;
+    a.descs = descs_dev;
+    a.order = order_dev;
+    a.n_gemv = n_gemv;
+    return launch_x_format<false>(bits, has_zero, group, a, n_wg, max_seg_tiles, st);
+}
+
+// The numbering goes to device memory through kernel arguments, like the descriptors.
+struct OrderChunk {
+    uint16_t e[1024];
+};
+__global__ void write_order_kernel(OrderChunk c, int count, uint16_t* __restrict__ out) {
+    for (int i = threadIdx.x; i < count; i += blockDim.x) out[i] = c.e[i];
+}
+int launch_write_order(const std::vector<uint16_t>& order, uint16_t* dev, hipStream_t st) {
+    for (size_t i = 0; i < order.size(); i += 1024) {
+        OrderChunk c;
+        const int n = (int)std::min<size_t>(1024, order.size() - i);
+        for (int j = 0; j < 1024; ++j) c.e[j] = j < n ? order[i + j] : 0;
+        hipLaunchKernelGGL(write_order_kernel, dim3(1), dim3(256), 0, st, c, n, dev + i);
+    }
+    return launch_status();
 }
 
 int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,

@@ -84,12 +84,18 @@ def main():
 
     t0 = time.time()
     print("built-in tiling:", default.as_dict())
+    sweep("one-token decode, 7B layer set uint2 g64: workgroups numbered for equal work per compute unit (1) or a plain grid (0)",
+          "decode_x_balance", [0, 1], lambda: time_decode("7b_w2g64", 1))
+    sweep("one-token decode, 3.8B layer set uint2 g64: the same",
+          "decode_x_balance", [0, 1], lambda: time_decode("3p8b_w2g64", 1))
     sweep("one-token decode, 7B layer set uint2 g64 (K = 4096 and 11008): segments of a K that needs cutting",
-          "decode_x_long_seg_tiles", [16, 18, 20, 22, 24, 26, 29, 32, 40], lambda: time_decode("7b_w2g64", 1))
+          "decode_x_long_seg_tiles", [15, 16, 17, 18, 20, 22, 24, 29, 32, 40], lambda: time_decode("7b_w2g64", 1))
+    sweep("one-token decode, 7B layer set uint4 g128: the same",
+          "decode_x_long_seg_tiles", [15, 17, 20, 22, 24, 32], lambda: time_decode("7b_w4g128", 1))
     sweep("one-token decode, 7B layer set uint4 g128: bytes of packed weights per row block up to which K stays one segment",
           "decode_x_whole_bytes", [40960, 81920, 163840], lambda: time_decode("7b_w4g128", 1))
     sweep("one-token decode, 3.8B layer set uint2 g64 (K = 3072 and 8192)",
-          "decode_x_long_seg_tiles", [16, 22, 24, 32], lambda: time_decode("3p8b_w2g64", 1))
+          "decode_x_long_seg_tiles", [15, 17, 20, 22, 24, 32], lambda: time_decode("3p8b_w2g64", 1))
     sweep("8 tokens through the lookup kernel, 7B layer set uint4 g128",
           "decode_seg_tiles_many", [16, 20, 24, 28, 32], lambda: time_decode("7b_w4g128", 8))
     sweep("8 tokens through the small-batch matrix-core kernel, 7B layer set uint4 g128",

@@ -162,6 +162,45 @@ def test_batched_layer_set_full_size(oracle_lib, name):
         assert int(ws[: -(-shape.M // 64) * 4].view(torch.int32).abs().sum().item()) == 0
 
 
+@pytest.mark.parametrize("name", ["7b_w2g64", "3p8b_w1g64"])
+def test_numbered_and_plain_launch_give_the_same_bits(oracle_lib, name):
+    """The workgroup numbering (tiling.decode_x_balance) only changes which compute unit runs which workgroup:
+    the outputs of a numbered launch and of the plain grid are bit-identical."""
+    w = synth.WORKLOADS[name]
+    shapes, blobs, xs, ys, wss = [], [], [], [], []
+    x_of_act = {}
+    for li, spec in enumerate(w.layers):
+        q, s, z = synth.layer_tensors(w, 5, li)
+        if spec.act not in x_of_act:
+            x_of_act[spec.act] = to_dev(synth.activation(w, 5, li, 1))
+        shape = tman.Shape(spec.M, spec.K, w.bits, w.group, w.has_zero)
+        shapes.append(shape); blobs.append(pack(shape, q, s, z)); xs.append(x_of_act[spec.act])
+        ys.append(torch.full((1, spec.M), float("nan"), dtype=torch.float16, device=dev()))
+        wss.append(gemv_workspace(shape, 1))
+    assert tman.tman_mpgemv_x_batch_order(shapes), "expected a numbered launch on this device"
+    desc = torch.empty(tman.tman_mpgemv_batch_desc_bytes(len(shapes)), dtype=torch.uint8, device=dev())
+    tman.tman_mpgemv_x_batch_prepare(shapes, blobs, xs, ys, wss, desc)
+    tman.tman_mpgemv_x_batch_run(shapes, desc)
+    torch.cuda.synchronize()
+    numbered = [y.cpu().numpy() for y in ys]
+    saved = tman.tman_get_tiling()
+    try:
+        plain = tman.tman_get_tiling()
+        plain.decode_x_balance = 0
+        tman.tman_set_tiling(plain)
+        assert tman.tman_mpgemv_x_batch_order(shapes) == []
+        for y in ys:
+            y.fill_(float("nan"))
+        tman.tman_mpgemv_x_batch_prepare(shapes, blobs, xs, ys, wss, desc)
+        tman.tman_mpgemv_x_batch_run(shapes, desc)
+        torch.cuda.synchronize()
+    finally:
+        tman.tman_set_tiling(saved)
+    for a, y in zip(numbered, ys):
+        assert np.all(np.isfinite(a.astype(np.float32)))
+        assert np.array_equal(a.view(np.uint16), y.cpu().numpy().view(np.uint16))
+
+
 def test_batch_of_mixed_small_shapes(oracle_lib):
     bits, group = 4, 64
     dims = [(70, 192), (64, 4608), (130, 8320), (1, 64), (257, 4096)]
