@@ -232,7 +232,10 @@ int ordered_workgroups(int count, const Layout* L, int n_units) {
 }
 
 bool order_workgroups(int count, const Layout* L, int n_units, std::vector<uint16_t>* order) {
-    if (!ordered_workgroups(count, L, n_units)) return false;
+    const int n = ordered_workgroups(count, L, n_units);
+    if (!n) return false;
+    // unit j runs the ids j, j + n_units, ...
+    auto places = [&](int j) { return n / n_units + (j < n % n_units ? 1 : 0); };
     struct Item {
         int cost;
         uint16_t id;
@@ -246,22 +249,19 @@ bool order_workgroups(int count, const Layout* L, int n_units, std::vector<uint1
             items.push_back(Item{tiles + 2, (uint16_t)((g << 13) | w)});
         }
     }
-    const int n = (int)items.size();
     std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.cost > b.cost; });
     std::vector<int> load(n_units, 0), used(n_units, 0);
     std::vector<std::vector<uint16_t>> mine(n_units);
     for (const Item& it : items) {
         int best = -1;
-        for (int j = 0; j < n_units; ++j) {
-            const int places = n / n_units + (j < n % n_units ? 1 : 0);
-            if (used[j] < places && (best < 0 || load[j] < load[best])) best = j;
-        }
+        for (int j = 0; j < n_units; ++j)
+            if (used[j] < places(j) && (best < 0 || load[j] < load[best])) best = j;
         load[best] += it.cost;
         ++used[best];
         mine[best].push_back(it.id);
     }
-    // The greedy pass can leave a unit with few places under-filled; even the two extreme units out by exchanging
-    // one workgroup of each while that lowers the larger of their two loads.
+    // Local improvement: the fullest unit exchanges a workgroup with another unit as long as that lowers the larger
+    // of the two loads (the number of workgroups per unit is fixed by the position rule).
     auto cost_of = [&](uint16_t id) {
         for (const Item& it : items)
             if (it.id == id) return it.cost;
@@ -270,26 +270,32 @@ bool order_workgroups(int count, const Layout* L, int n_units, std::vector<uint1
     std::vector<std::vector<int>> cost(n_units);
     for (int j = 0; j < n_units; ++j)
         for (uint16_t id : mine[j]) cost[j].push_back(cost_of(id));
-    for (int round = 0; round < 4 * n; ++round) {
-        int hi = 0, lo = 0;
-        for (int j = 1; j < n_units; ++j) {
+    for (int round = 0; round < 8 * n; ++round) {
+        int hi = 0;
+        for (int j = 1; j < n_units; ++j)
             if (load[j] > load[hi]) hi = j;
-            if (load[j] < load[lo]) lo = j;
-        }
-        int best_a = -1, best_b = -1, best_max = load[hi];
-        for (size_t a = 0; a < cost[hi].size(); ++a)
-            for (size_t b = 0; b < cost[lo].size(); ++b) {
-                const int d = cost[hi][a] - cost[lo][b];
-                if (d <= 0) continue;
-                const int m = std::max(load[hi] - d, load[lo] + d);
-                if (m < best_max) best_max = m, best_a = (int)a, best_b = (int)b;
+        // the exchange with any other unit that lowers the larger of the two loads most
+        int best_j = -1, best_a = -1, best_b = -1, best_max = load[hi];
+        for (int j = 0; j < n_units; ++j) {
+            if (j == hi || load[j] >= load[hi]) continue;
+            for (size_t a = 0; a < cost[hi].size(); ++a) {
+                for (size_t b = 0; b < cost[j].size(); ++b) {
+                    const int d = cost[hi][a] - cost[j][b];
+                    if (d <= 0) continue;
+                    const int m = std::max(load[hi] - d, load[j] + d);
+                    if (m < best_max) best_max = m, best_j = j, best_a = (int)a, best_b = (int)b;
+                }
             }
-        if (best_a < 0) break;
-        const int d = cost[hi][best_a] - cost[lo][best_b];
-        std::swap(cost[hi][best_a], cost[lo][best_b]);
-        std::swap(mine[hi][best_a], mine[lo][best_b]);
-        load[hi] -= d;
-        load[lo] += d;
+        }
+        if (best_j < 0) break;
+        const int lo = best_j;
+        {
+            const int d = cost[hi][best_a] - cost[lo][best_b];
+            std::swap(cost[hi][best_a], cost[lo][best_b]);
+            std::swap(mine[hi][best_a], mine[lo][best_b]);
+            load[hi] -= d;
+            load[lo] += d;
+        }
     }
     order->assign(n, 0);
     for (int j = 0; j < n_units; ++j) {
