@@ -209,7 +209,7 @@ int tman_mpgemv_x_batch_run(int32_t count, const tman_shape_t *shapes, const voi
  * once -- at most 8 per compute unit, fewer when the tables of the longest segment take more LDS -- is launched
  * as a one-dimensional grid whose workgroup ids the library assigns: on this chip a launch that fits is dealt out
  * by position, workgroup i to compute unit i mod (number of units), so the numbering decides which workgroups
- * share a unit, and it is chosen so that every unit gets the same number of tile blocks (tiling.decode_x_balance;
+ * share a unit, and it is chosen so that every unit gets the same number of tile blocks (tiling.decode_balance;
  * the numbering is part of the descriptor table).  Results do not depend on it.
  * tman_mpgemv_x_batch_order returns that numbering without touching the device: `n_units` compute units (0: the
  * current device's); order[i] = (GEMV << 13) | (workgroup of the GEMV: row block * segments + segment) for
@@ -257,7 +257,8 @@ int tman_mpgemm(const tman_shape_t *shape, const void *packed, const void *x, in
  * activation share it; here entries of `x` may repeat).  Arguments as for tman_mpgemv_batch_prepare / _run with
  * the activations `x` (fp16 [N][K] each) in place of the table buffers; workspace[i] may be NULL where
  * tman_mpgemm_workspace_bytes(&shapes[i], N) is 0; the descriptor table takes
- * tman_mpgemv_batch_desc_bytes(count) bytes.
+ * tman_mpgemv_batch_desc_bytes(count) bytes.  Batches of up to 8 GEMMs whose workgroups are all resident at once
+ * (four per compute unit) are numbered for balance like those of tman_mpgemv_x (tiling.decode_balance).
  */
 int tman_mpgemm_batch_prepare(int32_t count, const tman_shape_t *shapes, const void *const *packed,
                               const void *const *x, int32_t N, void *const *y, void *const *workspace,
@@ -327,8 +328,9 @@ int tman_mpgemv_noalloc(const tman_shape_t *shape, const void *packed, const voi
  *                              packed weights per row block, is ONE segment; it is at most 32 (Eq. 1: the tables
  *                              of a segment, 1 KB per tile, live in the workgroup's 32 KB of LDS)
  *   decode_x_long_seg_tiles    ... a longer K is cut into equal segments of at most this many tiles
- *   decode_x_balance           1: batches of tman_mpgemv_x number their workgroups for equal work per compute
- *                              unit (see tman_mpgemv_x_batch_order), 0: plain grid
+ *   decode_balance             1: batches of tman_mpgemv_x and of the small-batch tman_mpgemm number their
+ *                              workgroups for equal work per compute unit (see tman_mpgemv_x_batch_order),
+ *                              0: plain grids
  *   small_seg_tiles            K tiles per workgroup of tman_mpgemm for N <= 32
  *   prefill_row_blocks         tile blocks in M per workgroup of the tiled prefill kernel, 1..4 (Eq. 4: four
  *                              stage buffers of rows x 80 + 256 x 64 bytes within 160 KB of LDS), 0 = chosen per
@@ -347,7 +349,7 @@ typedef struct tman_tiling {
     int32_t decode_x_whole_bytes;
     int32_t small_seg_tiles;
     int32_t prefill_row_blocks;
-    int32_t decode_x_balance;
+    int32_t decode_balance;
 } tman_tiling_t;
 int tman_default_tiling(tman_tiling_t *out);
 int tman_get_tiling(tman_tiling_t *out);

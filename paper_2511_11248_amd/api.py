@@ -29,7 +29,7 @@ class Tiling(C.Structure):
     """Mirror of ``tman_tiling_t`` (see include/tman.h)."""
     _fields_ = [("decode_seg_tiles", C.c_int32), ("decode_seg_tiles_many", C.c_int32), ("decode_x_seg_tiles", C.c_int32),
                 ("decode_x_long_seg_tiles", C.c_int32), ("decode_x_whole_bytes", C.c_int32), ("small_seg_tiles", C.c_int32),
-                ("prefill_row_blocks", C.c_int32), ("decode_x_balance", C.c_int32)]
+                ("prefill_row_blocks", C.c_int32), ("decode_balance", C.c_int32)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

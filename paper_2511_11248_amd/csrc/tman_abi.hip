@@ -381,8 +381,14 @@ int tman_mpgemm_batch_prepare(int32_t count, const tman_shape_t* shapes, const v
         if ((long long)N * shapes[i].K * 2 > 0xFFFFFFF0LL) return TMAN_ERR_SHAPE;
         fill_desc_small(host[i], make_layout(&shapes[i]), packed[i], x[i], N, y[i], need ? workspace[i] : nullptr);
     }
-    return launch_write_descs(host, count, shapes[0].bits, shapes[0].group, (shapes[0].flags & TMAN_FLAG_HAS_ZERO) ? 1 : 0,
-                              static_cast<GemvDesc*>(desc), (hipStream_t)stream);
+    rc = launch_write_descs(host, count, shapes[0].bits, shapes[0].group, (shapes[0].flags & TMAN_FLAG_HAS_ZERO) ? 1 : 0,
+                            static_cast<GemvDesc*>(desc), (hipStream_t)stream);
+    if (rc != TMAN_OK) return rc;
+    std::vector<Layout> L(count);
+    for (int i = 0; i < count; ++i) L[i] = make_layout(&shapes[i]);
+    std::vector<uint16_t> order;
+    if (!order_workgroups_small(count, L.data(), device_units(), &order)) return TMAN_OK;
+    return launch_write_order(order, order_of(desc, count), (hipStream_t)stream);
 }
 
 int tman_mpgemm_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, const void* desc, void* stream) {
@@ -391,6 +397,14 @@ int tman_mpgemm_batch_run(int32_t count, const tman_shape_t* shapes, int32_t N, 
     if (N < 1 || N > TMAN_MAX_SMALL_TOKENS) return TMAN_ERR_SHAPE;
     if (!desc) return TMAN_ERR_NULL;
     if (!aligned16(desc)) return TMAN_ERR_ALIGN;
+    {
+        Layout L[8];
+        for (int i = 0; i < count && i < 8; ++i) L[i] = make_layout(&shapes[i]);
+        if (const int n_wg = ordered_workgroups_small(count, L, device_units()))
+            return launch_mpgemm_small_ordered(shapes[0].bits, shapes[0].group, shapes[0].flags & TMAN_FLAG_HAS_ZERO,
+                                               static_cast<const GemvDesc*>(desc), count,
+                                               order_of(const_cast<void*>(desc), count), n_wg, (hipStream_t)stream);
+    }
     int max_wg = 0;  // the launch grid is (workgroups of the largest GEMM) x count
     for (int i = 0; i < count; ++i) {
         const int n = plan_small(make_layout(&shapes[i])).n_workgroups;

@@ -139,9 +139,18 @@ int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y,
 int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,
                           int max_seg_tiles, hipStream_t st);
 constexpr int kOrderedMaxWorkgroups = 4096;  // room in a descriptor table for a numbering of the workgroups
-int ordered_workgroups(int count, const Layout* L, int n_units);  // workgroups of a numbered launch, 0: plain grid
-bool order_workgroups(int count, const Layout* L, int n_units, std::vector<uint16_t>* order);
+// workgroups of a numbered launch (0: plain grid) and the numbering, for the plans of any of the decode kernels
+int ordered_workgroups_of(int count, const Layout* L, const GemvPlan* plans, int n_units, int per_unit);
+bool order_workgroups_of(int count, const Layout* L, const GemvPlan* plans, int n_units, int per_unit,
+                         std::vector<uint16_t>* order);
 int launch_write_order(const std::vector<uint16_t>& order, uint16_t* dev, hipStream_t st);
+// ... of a one-token batch (tman_mpgemv_x) and of a small-batch mpGEMM batch
+int ordered_workgroups(int count, const Layout* L, int n_units);
+bool order_workgroups(int count, const Layout* L, int n_units, std::vector<uint16_t>* order);
+int ordered_workgroups_small(int count, const Layout* L, int n_units);
+bool order_workgroups_small(int count, const Layout* L, int n_units, std::vector<uint16_t>* order);
+int launch_mpgemm_small_ordered(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv,
+                                const uint16_t* order_dev, int n_wg, hipStream_t st);
 int launch_mpgemv_x_ordered(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv,
                             const uint16_t* order_dev, int n_wg, int max_seg_tiles, hipStream_t st);
 // a handful of tokens on the matrix cores, scheduled like the decoding kernels (tman_mpgemm with N <= 32, and its batch form)

@@ -22,6 +22,8 @@
 // Scheduling is that of the decoding kernels: a workgroup of four waves owns a row block and a K segment, the
 // four quarters meet in LDS, segments of a long K meet through the workspace (tickets, partial sums added in
 // segment order, so results do not depend on timing).
+#include <vector>
+
 #include "tman_dequant_device.h"
 #include "tman_gemv_device.h"
 
@@ -46,8 +48,8 @@ void fill_desc_small(GemvDesc& d, const Layout& L, const void* packed, const voi
     d.lut_s = nullptr;
 }
 
-template <int B, int GQ, bool HZ, bool SINGLE>
-__global__ void __launch_bounds__(kWaves * 64) mpgemm_small_kernel(KernelArgs<SINGLE> a) {
+template <int B, int GQ, bool HZ, bool SINGLE, typename Args>
+__global__ void __launch_bounds__(kWaves * 64) mpgemm_small_kernel(Args a) {
     using Cfg = GemvCfg<B, 1, GQ, HZ>;
     constexpr int D = 2;  // weight tile blocks in flight per wave
     __shared__ __attribute__((aligned(16))) float red[kWaves][kSmallTokens][kRedStride];
@@ -56,10 +58,10 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemm_small_kernel(KernelArgs<SI
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    const int g = SINGLE ? 0 : (int)blockIdx.y;
+    int g, wg_local;
+    workgroup_of<SINGLE>(a, g, wg_local);
     const GemvDesc& d = desc_of<SINGLE>(a, g);
     const int n_seg = uniform(d.n_seg), n_ktiles = uniform(d.n_ktiles);
-    const int wg_local = (int)blockIdx.x;
     // Exits: surplus workgroups of the grid, and (single call) a blob packed for another shape or layout, which
     // is reported and leaves y alone (a batch is checked when its descriptor table is written).
     int n_wg = uniform(d.n_row_blocks) * n_seg;
@@ -237,19 +239,19 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemm_small_kernel(KernelArgs<SI
 // ---------------------------------------------------------------------------------------------
 // launch
 
-template <int B, bool HZ, bool SINGLE>
-static int launch_small_group(int group, const KernelArgs<SINGLE>& a, int n_wg, hipStream_t st) {
-    const dim3 grid((unsigned)n_wg, (unsigned)a.n_gemv), block(kWaves * 64);
+template <int B, bool HZ, bool SINGLE, typename Args>
+static int launch_small_group(int group, const Args& a, int n_wg, hipStream_t st) {
+    const dim3 grid((unsigned)n_wg, __is_same(Args, OrderedArgs) ? 1u : (unsigned)a.n_gemv), block(kWaves * 64);
     switch (group) {
-        case 32: hipLaunchKernelGGL((mpgemm_small_kernel<B, 32, HZ, SINGLE>), grid, block, 0, st, a); break;
-        case 64: hipLaunchKernelGGL((mpgemm_small_kernel<B, 64, HZ, SINGLE>), grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL((mpgemm_small_kernel<B, 128, HZ, SINGLE>), grid, block, 0, st, a); break;
+        case 32: hipLaunchKernelGGL((mpgemm_small_kernel<B, 32, HZ, SINGLE, Args>), grid, block, 0, st, a); break;
+        case 64: hipLaunchKernelGGL((mpgemm_small_kernel<B, 64, HZ, SINGLE, Args>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((mpgemm_small_kernel<B, 128, HZ, SINGLE, Args>), grid, block, 0, st, a); break;
     }
     return launch_status();
 }
 
-template <bool SINGLE>
-static int launch_small_format(int bits, int has_zero, int group, const KernelArgs<SINGLE>& a, int n_wg, hipStream_t st) {
+template <bool SINGLE, typename Args>
+static int launch_small_format(int bits, int has_zero, int group, const Args& a, int n_wg, hipStream_t st) {
     if (bits == 1) {
         return has_zero ? launch_small_group<1, true, SINGLE>(group, a, n_wg, st)
                         : launch_small_group<1, false, SINGLE>(group, a, n_wg, st);
@@ -274,6 +276,30 @@ int launch_mpgemm_small_batch(int bits, int group, int has_zero, const GemvDesc*
     a.descs = descs_dev;
     a.n_gemv = n_gemv;
     return launch_small_format<false>(bits, has_zero, group, a, max_workgroups, st);
+}
+
+// The numbered launch of a batch (see order_workgroups_of): the reduction buffer of a workgroup takes 34.8 KB of LDS,
+// four workgroups are resident per compute unit.
+constexpr int kSmallResident = (int)(160u * 1024u / (sizeof(float) * kWaves * kSmallTokens * kRedStride + 64));
+int ordered_workgroups_small(int count, const Layout* L, int n_units) {
+    if (count > 8) return 0;
+    std::vector<GemvPlan> plans(count);
+    for (int g = 0; g < count; ++g) plans[g] = plan_small(L[g]);
+    return ordered_workgroups_of(count, L, plans.data(), n_units, kSmallResident);
+}
+bool order_workgroups_small(int count, const Layout* L, int n_units, std::vector<uint16_t>* order) {
+    if (count > 8) return false;
+    std::vector<GemvPlan> plans(count);
+    for (int g = 0; g < count; ++g) plans[g] = plan_small(L[g]);
+    return order_workgroups_of(count, L, plans.data(), n_units, kSmallResident, order);
+}
+int launch_mpgemm_small_ordered(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv,
+                                const uint16_t* order_dev, int n_wg, hipStream_t st) {
+    OrderedArgs a;
+    a.descs = descs_dev;
+    a.order = order_dev;
+    a.n_gemv = n_gemv;
+    return launch_small_format<false>(bits, has_zero, group, a, n_wg, st);
 }
 
 }  // namespace tman

@@ -28,6 +28,9 @@
 // mpgemv_kernel serves 1 to 8 tokens and reads the tables tman_build_lut made (Sec. 5: the precompute as a
 // kernel of its own, shared by the layers fed from one activation).  The one-token kernel that builds its
 // tables itself is in tman_mpgemv_x.hip.
+#include <algorithm>
+#include <vector>
+
 #include "tman_mpgemv_kernel.h"
 
 namespace tman {
@@ -123,6 +126,106 @@ int launch_write_descs(const GemvDesc* host, int count, int bits, int group, int
         int n = count - i < 16 ? count - i : 16;
         for (int j = 0; j < 16; ++j) c.d[j] = host[i + (j < n ? j : 0)];
         hipLaunchKernelGGL(write_descs_kernel, dim3(1), dim3(64), 0, st, c, n, bits, group, has_zero, dev + i, status);
+    }
+    return launch_status();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Numbering the workgroups of a batch for equal work per compute unit.
+//
+// With workgroup i on compute unit i mod n_units (what the dispatcher does with a launch that is resident at
+// once), the numbering decides which workgroups share a unit.  The workgroups, largest first, go one by one to the
+// unit with the least work so far that still has a free place (unit j has a place for ids j, j + n_units, ...);
+// then the fullest unit exchanges a workgroup with another unit as long as that lowers the larger of the two
+// loads; inside a unit the largest gets the lowest id.  Work of a workgroup = tile blocks of its K segment + 2
+// (start and end of a workgroup cost about that).  A batch qualifies with at most 8 GEMVs (three bits of an
+// entry) and no more workgroups than are resident at once: `per_unit` per compute unit.
+int ordered_workgroups_of(int count, const Layout* L, const GemvPlan* plans, int n_units, int per_unit) {
+    (void)L;
+    if (count > 8 || n_units < 1 || per_unit < 1 || !current_tiling().decode_balance) return 0;
+    int n = 0;
+    for (int g = 0; g < count; ++g) {
+        if (plans[g].n_workgroups > 0x1fff) return 0;
+        n += plans[g].n_workgroups;
+    }
+    return n <= per_unit * n_units && n <= kOrderedMaxWorkgroups ? n : 0;
+}
+
+bool order_workgroups_of(int count, const Layout* L, const GemvPlan* plans, int n_units, int per_unit,
+                         std::vector<uint16_t>* order) {
+    const int n = ordered_workgroups_of(count, L, plans, n_units, per_unit);
+    if (!n) return false;
+    auto places = [&](int j) { return n / n_units + (j < n % n_units ? 1 : 0); };
+    struct Item {
+        int cost;
+        uint16_t id;
+    };
+    std::vector<Item> items;
+    for (int g = 0; g < count; ++g) {
+        const GemvPlan& p = plans[g];
+        for (int w = 0; w < p.n_workgroups; ++w) {
+            const int seg = w % p.n_seg;
+            const int tiles = std::min(p.seg_tiles, L[g].n_ktiles - seg * p.seg_tiles);
+            items.push_back(Item{tiles + 2, (uint16_t)((g << 13) | w)});
+        }
+    }
+    std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.cost > b.cost; });
+    std::vector<int> load(n_units, 0);
+    std::vector<std::vector<uint16_t>> mine(n_units);
+    std::vector<std::vector<int>> cost(n_units);
+    for (const Item& it : items) {
+        int best = -1;
+        for (int j = 0; j < n_units; ++j)
+            if ((int)mine[j].size() < places(j) && (best < 0 || load[j] < load[best])) best = j;
+        load[best] += it.cost;
+        mine[best].push_back(it.id);
+        cost[best].push_back(it.cost);
+    }
+    for (int round = 0; round < 8 * n; ++round) {
+        int hi = 0;
+        for (int j = 1; j < n_units; ++j)
+            if (load[j] > load[hi]) hi = j;
+        int best_j = -1, best_a = -1, best_b = -1, best_max = load[hi];
+        for (int j = 0; j < n_units; ++j) {
+            if (j == hi || load[j] >= load[hi]) continue;
+            for (size_t a = 0; a < cost[hi].size(); ++a)
+                for (size_t b = 0; b < cost[j].size(); ++b) {
+                    const int d = cost[hi][a] - cost[j][b];
+                    if (d <= 0) continue;
+                    const int m = std::max(load[hi] - d, load[j] + d);
+                    if (m < best_max) best_max = m, best_j = j, best_a = (int)a, best_b = (int)b;
+                }
+        }
+        if (best_j < 0) break;
+        const int d = cost[hi][best_a] - cost[best_j][best_b];
+        std::swap(cost[hi][best_a], cost[best_j][best_b]);
+        std::swap(mine[hi][best_a], mine[best_j][best_b]);
+        load[hi] -= d;
+        load[best_j] += d;
+    }
+    order->assign(n, 0);
+    for (int j = 0; j < n_units; ++j) {
+        std::vector<size_t> by_cost(mine[j].size());
+        for (size_t r = 0; r < by_cost.size(); ++r) by_cost[r] = r;
+        std::stable_sort(by_cost.begin(), by_cost.end(), [&](size_t a, size_t b) { return cost[j][a] > cost[j][b]; });
+        for (size_t r = 0; r < by_cost.size(); ++r) (*order)[r * n_units + j] = mine[j][by_cost[r]];
+    }
+    return true;
+}
+
+// The numbering goes to device memory through kernel arguments, like the descriptors.
+struct OrderChunk {
+    uint16_t e[1024];
+};
+__global__ void write_order_kernel(OrderChunk c, int count, uint16_t* __restrict__ out) {
+    for (int i = threadIdx.x; i < count; i += blockDim.x) out[i] = c.e[i];
+}
+int launch_write_order(const std::vector<uint16_t>& order, uint16_t* dev, hipStream_t st) {
+    for (size_t i = 0; i < order.size(); i += 1024) {
+        OrderChunk c;
+        const int n = (int)std::min<size_t>(1024, order.size() - i);
+        for (int j = 0; j < 1024; ++j) c.e[j] = j < n ? order[i + j] : 0;
+        hipLaunchKernelGGL(write_order_kernel, dim3(1), dim3(256), 0, st, c, n, dev + i);
     }
     return launch_status();
 }

@@ -43,23 +43,8 @@ void fill_desc_x(GemvDesc& d, const Layout& L, const void* packed, const void* x
     d.lut_s = nullptr;
 }
 
-// A launch whose workgroups are numbered by the host: workgroup id -> (GEMV, workgroup within the GEMV).  When all
-// workgroups of a launch are resident at once, this chip's dispatcher hands workgroup i to compute unit i mod 256
-// (measured: ids 8, 264, 520, 776 share a unit), so the numbering decides which workgroups share a unit, and the
-// host numbers them so that every unit gets the same amount of work (see order_workgroups).
-struct OrderedArgs {
-    const GemvDesc* descs;
-    const uint16_t* order;  // per workgroup id: GEMV in bits 13..15, workgroup within the GEMV in bits 0..12
-    int n_gemv;
-};
-template <bool SINGLE>
-__device__ __forceinline__ const GemvDesc& desc_of(const OrderedArgs& a, int g) {
-    return a.descs[g];
-}
-
 template <int B, int GQ, bool HZ, bool SINGLE, typename Args>
 __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(Args a) {
-    constexpr bool ORDERED = __is_same(Args, OrderedArgs);
     using Cfg = GemvCfg<B, 1, GQ, HZ>;
     constexpr int D = Cfg::D;
     constexpr int TPG = GQ / kLutGroup;  // tables per quantization group: 8, 16 or 32 consecutive lanes
@@ -73,12 +58,8 @@ __global__ void __launch_bounds__(kWaves * 64) mpgemv_x_kernel(Args a) {
 #pragma unroll
     for (int i = 0; i < B; ++i) pw[i] = opaque((float)(1 << i));
 
-    int g = SINGLE ? 0 : (int)blockIdx.y, wg_local = (int)blockIdx.x;
-    if constexpr (ORDERED) {
-        const uint32_t e = uniform((int)a.order[blockIdx.x]);
-        g = (int)(e >> 13);
-        wg_local = (int)(e & 0x1fffu);
-    }
+    int g, wg_local;
+    workgroup_of<SINGLE>(a, g, wg_local);
     const GemvDesc& d = desc_of<SINGLE>(a, g);
     const int n_seg = uniform(d.n_seg), n_ktiles = uniform(d.n_ktiles);
     // Exits: surplus workgroups of the grid, and (single call) a blob packed for another shape or layout, which is
@@ -211,100 +192,24 @@ int launch_mpgemv_x(const Layout& L, const void* packed, const void* x, void* y,
     return launch_x_format<true>(L.bits, L.has_zero, L.group, a, p.n_workgroups, p.seg_tiles, st);
 }
 
-// Numbers the workgroups of a batch so that, with workgroup i on compute unit i mod n_units, every unit gets the
-// same work: the workgroups, largest first, go one by one to the unit with the least work so far that still has a
-// free place (unit j has a place for ids j, j + n_units, ...), then the two extreme units exchange workgroups
-// while that helps; inside a unit the largest gets the lowest id.  Work of a workgroup = tile blocks of its K
-// segment + 2 (start and end of a workgroup cost about that).  Returns false when the batch does not qualify: more
-// than 8 GEMVs, or more workgroups than are resident at once (LDS of the longest segment, 8 workgroups of four
-// waves per unit at most), in which case the dispatcher no longer goes by position.
-int ordered_workgroups(int count, const Layout* L, int n_units) {
-    if (count > 8 || n_units < 1 || !current_tiling().decode_x_balance) return 0;
-    int n = 0, max_seg_tiles = 0;
-    for (int g = 0; g < count; ++g) {
-        const GemvPlan p = plan_gemv_x(L[g]);
-        if (p.n_workgroups > 0x1fff) return 0;
-        n += p.n_workgroups;
-        max_seg_tiles = std::max(max_seg_tiles, p.seg_tiles);
-    }
-    const int per_unit = std::min(8, (int)(160u * 1024u / x_lds_bytes(max_seg_tiles)));
-    return n <= per_unit * n_units && n <= kOrderedMaxWorkgroups ? n : 0;
+// The numbered launch of a one-token batch (see order_workgroups_of): at most 8 workgroups of four waves are resident
+// per compute unit, fewer when the tables of the longest segment take more LDS.
+static int x_resident_per_unit(int count, const Layout* L) {
+    int max_seg_tiles = 1;
+    for (int g = 0; g < count; ++g) max_seg_tiles = std::max(max_seg_tiles, plan_gemv_x(L[g]).seg_tiles);
+    return std::min(8, (int)(160u * 1024u / x_lds_bytes(max_seg_tiles)));
 }
-
+int ordered_workgroups(int count, const Layout* L, int n_units) {
+    if (count > 8) return 0;
+    std::vector<GemvPlan> plans(count);
+    for (int g = 0; g < count; ++g) plans[g] = plan_gemv_x(L[g]);
+    return ordered_workgroups_of(count, L, plans.data(), n_units, x_resident_per_unit(count, L));
+}
 bool order_workgroups(int count, const Layout* L, int n_units, std::vector<uint16_t>* order) {
-    const int n = ordered_workgroups(count, L, n_units);
-    if (!n) return false;
-    // unit j runs the ids j, j + n_units, ...
-    auto places = [&](int j) { return n / n_units + (j < n % n_units ? 1 : 0); };
-    struct Item {
-        int cost;
-        uint16_t id;
-    };
-    std::vector<Item> items;
-    for (int g = 0; g < count; ++g) {
-        const GemvPlan p = plan_gemv_x(L[g]);
-        for (int w = 0; w < p.n_workgroups; ++w) {
-            const int seg = w % p.n_seg;
-            const int tiles = std::min(p.seg_tiles, L[g].n_ktiles - seg * p.seg_tiles);
-            items.push_back(Item{tiles + 2, (uint16_t)((g << 13) | w)});
-        }
-    }
-    std::stable_sort(items.begin(), items.end(), [](const Item& a, const Item& b) { return a.cost > b.cost; });
-    std::vector<int> load(n_units, 0), used(n_units, 0);
-    std::vector<std::vector<uint16_t>> mine(n_units);
-    for (const Item& it : items) {
-        int best = -1;
-        for (int j = 0; j < n_units; ++j)
-            if (used[j] < places(j) && (best < 0 || load[j] < load[best])) best = j;
-        load[best] += it.cost;
-        ++used[best];
-        mine[best].push_back(it.id);
-    }
-    // Local improvement: the fullest unit exchanges a workgroup with another unit as long as that lowers the larger
-    // of the two loads (the number of workgroups per unit is fixed by the position rule).
-    auto cost_of = [&](uint16_t id) {
-        for (const Item& it : items)
-            if (it.id == id) return it.cost;
-        return 0;
-    };
-    std::vector<std::vector<int>> cost(n_units);
-    for (int j = 0; j < n_units; ++j)
-        for (uint16_t id : mine[j]) cost[j].push_back(cost_of(id));
-    for (int round = 0; round < 8 * n; ++round) {
-        int hi = 0;
-        for (int j = 1; j < n_units; ++j)
-            if (load[j] > load[hi]) hi = j;
-        // the exchange with any other unit that lowers the larger of the two loads most
-        int best_j = -1, best_a = -1, best_b = -1, best_max = load[hi];
-        for (int j = 0; j < n_units; ++j) {
-            if (j == hi || load[j] >= load[hi]) continue;
-            for (size_t a = 0; a < cost[hi].size(); ++a) {
-                for (size_t b = 0; b < cost[j].size(); ++b) {
-                    const int d = cost[hi][a] - cost[j][b];
-                    if (d <= 0) continue;
-                    const int m = std::max(load[hi] - d, load[j] + d);
-                    if (m < best_max) best_max = m, best_j = j, best_a = (int)a, best_b = (int)b;
-                }
-            }
-        }
-        if (best_j < 0) break;
-        const int lo = best_j;
-        {
-            const int d = cost[hi][best_a] - cost[lo][best_b];
-            std::swap(cost[hi][best_a], cost[lo][best_b]);
-            std::swap(mine[hi][best_a], mine[lo][best_b]);
-            load[hi] -= d;
-            load[lo] += d;
-        }
-    }
-    order->assign(n, 0);
-    for (int j = 0; j < n_units; ++j) {
-        std::vector<size_t> by_cost(mine[j].size());
-        for (size_t r = 0; r < by_cost.size(); ++r) by_cost[r] = r;
-        std::stable_sort(by_cost.begin(), by_cost.end(), [&](size_t a, size_t b) { return cost[j][a] > cost[j][b]; });
-        for (size_t r = 0; r < by_cost.size(); ++r) (*order)[r * n_units + j] = mine[j][by_cost[r]];
-    }
-    return true;
+    if (count > 8) return false;
+    std::vector<GemvPlan> plans(count);
+    for (int g = 0; g < count; ++g) plans[g] = plan_gemv_x(L[g]);
+    return order_workgroups_of(count, L, plans.data(), n_units, x_resident_per_unit(count, L), order);
 }
 
 int launch_mpgemv_x_ordered(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv,
@@ -314,23 +219,6 @@ int launch_mpgemv_x_ordered(int bits, int group, int has_zero, const GemvDesc* d
     a.order = order_dev;
     a.n_gemv = n_gemv;
     return launch_x_format<false>(bits, has_zero, group, a, n_wg, max_seg_tiles, st);
-}
-
-// The numbering goes to device memory through kernel arguments, like the descriptors.
-struct OrderChunk {
-    uint16_t e[1024];
-};
-__global__ void write_order_kernel(OrderChunk c, int count, uint16_t* __restrict__ out) {
-    for (int i = threadIdx.x; i < count; i += blockDim.x) out[i] = c.e[i];
-}
-int launch_write_order(const std::vector<uint16_t>& order, uint16_t* dev, hipStream_t st) {
-    for (size_t i = 0; i < order.size(); i += 1024) {
-        OrderChunk c;
-        const int n = (int)std::min<size_t>(1024, order.size() - i);
-        for (int j = 0; j < 1024; ++j) c.e[j] = j < n ? order[i + j] : 0;
-        hipLaunchKernelGGL(write_order_kernel, dim3(1), dim3(256), 0, st, c, n, dev + i);
-    }
-    return launch_status();
 }
 
 int launch_mpgemv_x_batch(int bits, int group, int has_zero, const GemvDesc* descs_dev, int n_gemv, int max_workgroups,

@@ -11,7 +11,7 @@
 //   decode_*            K tiles per decoding workgroup (its K segment); the one-token kernel keeps the tables of
 //                       its whole segment in LDS, so there the segment is bounded like K_lut in Eq. 1:
 //                       seg_tiles x 1 KB of tables <= the 32 KB a workgroup requests;
-//   decode_x_balance    whether the workgroups of a one-token batch are numbered for equal work per compute unit
+//   decode_balance    whether the workgroups of a one-token batch are numbered for equal work per compute unit
 //                       (not a tile size, but it decides which segment length is best);
 //   prefill_row_blocks  tile blocks in M per prefill workgroup; Eq. 4 reads ring (4) x stage bytes <= 160 KB of
 //                       LDS, which admits at most 4.
@@ -42,7 +42,7 @@ static int check_tiling(const tman_tiling_t& t) {
         return TMAN_ERR_SHAPE;
     if (t.decode_x_long_seg_tiles < 1 || t.decode_x_long_seg_tiles > t.decode_x_seg_tiles) return TMAN_ERR_SHAPE;
     if (t.decode_x_whole_bytes < 1024) return TMAN_ERR_SHAPE;
-    if (t.decode_x_balance != 0 && t.decode_x_balance != 1) return TMAN_ERR_SHAPE;
+    if (t.decode_balance != 0 && t.decode_balance != 1) return TMAN_ERR_SHAPE;
     // Eq. 4: stage ring of the prefill kernel: rows x 80 bytes of fp16 weights + 256 tokens x 64 bytes per stage
     if (t.prefill_row_blocks < 0 || t.prefill_row_blocks > 4) return TMAN_ERR_SHAPE;
     const int rb = t.prefill_row_blocks ? t.prefill_row_blocks : 4;

@@ -85,9 +85,9 @@ def main():
     t0 = time.time()
     print("built-in tiling:", default.as_dict())
     sweep("one-token decode, 7B layer set uint2 g64: workgroups numbered for equal work per compute unit (1) or a plain grid (0)",
-          "decode_x_balance", [0, 1], lambda: time_decode("7b_w2g64", 1))
+          "decode_balance", [0, 1], lambda: time_decode("7b_w2g64", 1))
     sweep("one-token decode, 3.8B layer set uint2 g64: the same",
-          "decode_x_balance", [0, 1], lambda: time_decode("3p8b_w2g64", 1))
+          "decode_balance", [0, 1], lambda: time_decode("3p8b_w2g64", 1))
     sweep("one-token decode, 7B layer set uint2 g64 (K = 4096 and 11008): segments of a K that needs cutting",
           "decode_x_long_seg_tiles", [15, 16, 17, 18, 20, 22, 24, 29, 32, 40], lambda: time_decode("7b_w2g64", 1))
     sweep("one-token decode, 7B layer set uint4 g128: the same",

@@ -114,6 +114,21 @@ def test_batched_layer_set_full_size(oracle_lib, N):
         assert np.array_equal(y1.view(np.uint16), y.cpu().numpy().view(np.uint16))
         err = oracle.row_relative_error(y1, oracle.matmul(q, s, z, x, w.bits, w.group)).max()
         assert err <= TOL, f"{shape}: {err:.3e}"
+    # the launch above numbers its workgroups for balance (tiling.decode_balance); the plain grid gives the same bits
+    saved = tman.tman_get_tiling()
+    try:
+        plain = tman.tman_get_tiling()
+        plain.decode_balance = 0
+        tman.tman_set_tiling(plain)
+        for y in ys:
+            y.fill_(float("nan"))
+        tman.tman_mpgemm_batch_prepare(shapes, blobs, xs, N, ys, wss, desc)
+        tman.tman_mpgemm_batch_run(shapes, N, desc)
+        torch.cuda.synchronize()
+    finally:
+        tman.tman_set_tiling(saved)
+    for y1, y in zip(first, ys):
+        assert np.array_equal(y1.view(np.uint16), y.cpu().numpy().view(np.uint16))
 
 
 def test_batch_of_mixed_small_shapes_and_a_foreign_blob(oracle_lib):

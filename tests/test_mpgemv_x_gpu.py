@@ -164,7 +164,7 @@ def test_batched_layer_set_full_size(oracle_lib, name):
 
 @pytest.mark.parametrize("name", ["7b_w2g64", "3p8b_w1g64"])
 def test_numbered_and_plain_launch_give_the_same_bits(oracle_lib, name):
-    """The workgroup numbering (tiling.decode_x_balance) only changes which compute unit runs which workgroup:
+    """The workgroup numbering (tiling.decode_balance) only changes which compute unit runs which workgroup:
     the outputs of a numbered launch and of the plain grid are bit-identical."""
     w = synth.WORKLOADS[name]
     shapes, blobs, xs, ys, wss = [], [], [], [], []
@@ -186,7 +186,7 @@ def test_numbered_and_plain_launch_give_the_same_bits(oracle_lib, name):
     saved = tman.tman_get_tiling()
     try:
         plain = tman.tman_get_tiling()
-        plain.decode_x_balance = 0
+        plain.decode_balance = 0
         tman.tman_set_tiling(plain)
         assert tman.tman_mpgemv_x_batch_order(shapes) == []
         for y in ys:

@@ -61,7 +61,7 @@ def test_batches_that_do_not_qualify_keep_the_plain_grid():
     t = tman.tman_get_tiling()
     try:
         off = tman.tman_get_tiling()
-        off.decode_x_balance = 0
+        off.decode_balance = 0
         tman.tman_set_tiling(off)
         assert tman.tman_mpgemv_x_batch_order(_layer_shapes("7b_w2g64"), 256) == []
     finally:
