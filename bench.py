@@ -36,7 +36,7 @@ MFMA_I8_PEAK_TOPS = 5000.0
 # WRITE_SIZE runs of this script scaled by a plain copy of known size (--calibration-copy); the counters
 # cannot be read from inside the process.  Source: profiles/mpgemv_x_7b_w2g64_and_mpgemm_w4g64_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    ("mpgemv_x", "7b_w2g64", 1): 63_697_920 + 160_768,
+    ("mpgemv_x", "7b_w2g64", 1): 63_865_856 + 197_632,
     ("mpgemm", "prefill_w4g64", 1024): 92_651_315 + 22_544_384,
 }
 
