@@ -31,6 +31,7 @@ typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 constexpr int kI8Rows = 128, kI8Tokens = 128, kI8StageK = 64;
+constexpr int kI8Ahead = 4;  // stages of global loads in flight per wave
 constexpr int kI8RowBytes = kI8StageK + 16;  // padded LDS row: 20 dwords, conflict-free 16-byte accesses
 constexpr int kI8StageBytes = (kI8Rows + kI8Tokens) * kI8RowBytes;
 constexpr int kI8OutRow = kI8Rows * 2 + 16;  // bytes per token of the fp16 output tile in LDS
@@ -202,10 +203,15 @@ __global__ void __launch_bounds__(256) mpgemm_i8_kernel(GemmI8Args a) {
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
     const int wm = wave >> 1, wn = wave & 1, r = lane & 31, h = lane >> 5;
 
-    uint32_t plane[B];
-    u32x4 xv[2];
-    load_planes(plane, 0);
-    load_x(xv, 0);
+    // Global loads run kI8Ahead stages ahead of their use, in a ring of register sets (a stage of MFMAs is far
+    // shorter than the latency of a load); stages past K read zeros, so the loop runs whole rings.
+    uint32_t plane[kI8Ahead][B];
+    u32x4 xv[kI8Ahead][2];
+#pragma unroll
+    for (int u = 0; u < kI8Ahead; ++u) {
+        load_planes(plane[u], u);
+        load_x(xv[u], u);
+    }
     // scale and zero of the tile's rows (the first quantization block of a row stands for the whole row)
     if (tid < kI8Rows) {
         const int rb = mt * 2 + (tid >> 6), l = tid & 63;
@@ -218,38 +224,41 @@ __global__ void __launch_bounds__(256) mpgemm_i8_kernel(GemmI8Args a) {
         row_scale[tid] = sc;
         row_zs[tid] = zs;
     }
-    for (int s = 0; s < k_stages; ++s) {
-        uint8_t* buf = smem + (s & 1) * kI8StageBytes;
-        {
-            u32x4 lo, hi;
-            codes_to_bytes<B>(plane, lo, hi);
-            uint8_t* wrow = buf + ((wave >> 1) * 64 + lane) * kI8RowBytes + wblk * 32;
-            *reinterpret_cast<u32x4*>(wrow) = lo;
-            *reinterpret_cast<u32x4*>(wrow + 16) = hi;
-            uint8_t* xrow = buf + (kI8Rows + xtok) * kI8RowBytes + xhalf * 32;
-            *reinterpret_cast<u32x4*>(xrow) = xv[0];
-            *reinterpret_cast<u32x4*>(xrow + 16) = xv[1];
-        }
-        if (s + 1 < k_stages) {
-            load_planes(plane, s + 1);
-            load_x(xv, s + 1);
-        }
-        __syncthreads();
-        const uint8_t* wbase = buf + (wm * 64 + r) * kI8RowBytes + h * 16;
-        const uint8_t* xbase = buf + (kI8Rows + wn * 64 + r) * kI8RowBytes + h * 16;
+    const int n_stages = (k_stages + kI8Ahead - 1) / kI8Ahead * kI8Ahead;
+    for (int s0 = 0; s0 < n_stages; s0 += kI8Ahead) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            i32x4 wf[2], xf[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                wf[i] = *reinterpret_cast<const i32x4*>(wbase + i * 32 * kI8RowBytes + ks * 32);
-                xf[i] = *reinterpret_cast<const i32x4*>(xbase + i * 32 * kI8RowBytes + ks * 32);
+        for (int u = 0; u < kI8Ahead; ++u) {
+            const int s = s0 + u;
+            uint8_t* buf = smem + (s & 1) * kI8StageBytes;
+            {
+                u32x4 lo, hi;
+                codes_to_bytes<B>(plane[u], lo, hi);
+                uint8_t* wrow = buf + ((wave >> 1) * 64 + lane) * kI8RowBytes + wblk * 32;
+                *reinterpret_cast<u32x4*>(wrow) = lo;
+                *reinterpret_cast<u32x4*>(wrow + 16) = hi;
+                uint8_t* xrow = buf + (kI8Rows + xtok) * kI8RowBytes + xhalf * 32;
+                *reinterpret_cast<u32x4*>(xrow) = xv[u][0];
+                *reinterpret_cast<u32x4*>(xrow + 16) = xv[u][1];
             }
+            load_planes(plane[u], s + kI8Ahead);
+            load_x(xv[u], s + kI8Ahead);
+            __syncthreads();
+            const uint8_t* wbase = buf + (wm * 64 + r) * kI8RowBytes + h * 16;
+            const uint8_t* xbase = buf + (kI8Rows + wn * 64 + r) * kI8RowBytes + h * 16;
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int ks = 0; ks < 2; ++ks) {
+                i32x4 wf[2], xf[2];
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[i], xf[j], acc[i][j], 0, 0, 0);
+                for (int i = 0; i < 2; ++i) {
+                    wf[i] = *reinterpret_cast<const i32x4*>(wbase + i * 32 * kI8RowBytes + ks * 32);
+                    xf[i] = *reinterpret_cast<const i32x4*>(xbase + i * 32 * kI8RowBytes + ks * 32);
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[i], xf[j], acc[i][j], 0, 0, 0);
+            }
         }
     }
     __syncthreads();  // every wave is done with the stage buffers, which the output tile reuses
