@@ -295,6 +295,14 @@ int tman_mpgemm_i8(const tman_shape_t *shape, const void *packed, const void *xq
  * assumed when no device is present).  Informational; 0 for an invalid shape or N < 1.
  */
 int32_t tman_mpgemm_tile_rows(const tman_shape_t *shape, int32_t N);
+/*
+ * Which kernel tman_mpgemm_i8 runs for this shape and N, in the terms of tiling.i8_token_blocks: 1 = the kernel with
+ * 128 x 128 tiles, 3 / 4 / 7 = the kernel whose workgroups take 256 rows x 96 / 128 / 224 tokens and dequantize in
+ * registers.  The choice models the time of the grids they give on the current device (256 units are assumed when
+ * no device is present); a non-zero tiling.i8_token_blocks overrides it.  Informational; 0 for an invalid shape or
+ * N < 1.
+ */
+int32_t tman_mpgemm_i8_token_blocks(const tman_shape_t *shape, int32_t N);
 
 /*
  * tman_mpgemv for callers that cannot allocate device memory: code under HIP graph capture, tight serving
@@ -335,6 +343,10 @@ int tman_mpgemv_noalloc(const tman_shape_t *shape, const void *packed, const voi
  *   prefill_row_blocks         tile blocks in M per workgroup of the tiled prefill kernel, 1..4 (Eq. 4: four
  *                              stage buffers of rows x 80 + 256 x 64 bytes within 160 KB of LDS), 0 = chosen per
  *                              call from the grid it gives
+ *   i8_token_blocks            tman_mpgemm_i8: 1 = the kernel with 128 x 128 tiles (weights and activations through
+ *                              LDS), 3 / 4 / 7 = the kernel whose waves dequantize their own 64 rows in registers and
+ *                              share 96 / 128 / 224 tokens of activations through LDS, 0 = chosen per call from the
+ *                              grids they give
  * tman_default_tiling gives the built-in values (the best of the measured sweep paper_2511_11248_amd/tune.py
  * makes on the device), tman_get_tiling the current ones; tman_set_tiling checks the constraints
  * (TMAN_ERR_SHAPE if violated) and makes the values current for all later calls of the process.  The tiling
@@ -350,6 +362,7 @@ typedef struct tman_tiling {
     int32_t small_seg_tiles;
     int32_t prefill_row_blocks;
     int32_t decode_balance;
+    int32_t i8_token_blocks;
 } tman_tiling_t;
 int tman_default_tiling(tman_tiling_t *out);
 int tman_get_tiling(tman_tiling_t *out);

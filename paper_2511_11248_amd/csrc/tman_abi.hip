@@ -341,6 +341,12 @@ int32_t tman_mpgemm_tile_rows(const tman_shape_t* shape, int32_t N) {
     return kRows * mpgemm_row_blocks_per_workgroup(make_layout(shape), N);
 }
 
+int32_t tman_mpgemm_i8_token_blocks(const tman_shape_t* shape, int32_t N) {
+    if (check_shape(shape) != TMAN_OK || N < 1) return 0;
+    const Layout L = make_layout(shape);
+    return choose_i8_token_blocks(L.n_row_blocks, N, L.K);
+}
+
 int tman_mpgemm(const tman_shape_t* shape, const void* packed, const void* x, int32_t N, void* y, void* workspace,
                 size_t workspace_bytes, void* stream) {
     int rc = check_shape(shape);

@@ -162,6 +162,8 @@ int launch_mpgemm_small_batch(int bits, int group, int has_zero, const GemvDesc*
 // integer matrix cores for formats with one scale and zero per row (tman_quantize_act_i8, tman_mpgemm_i8)
 size_t act_i8_bytes(int N, int K);
 int launch_quantize_act_i8(const void* x, int N, int K, void* out, hipStream_t st);
+// 1 = the 128 x 128 kernel, 3 / 4 / 7 = the wide kernel with that many 32-token blocks per workgroup
+int choose_i8_token_blocks(int n_row_blocks, int N, int K);
 int launch_mpgemm_i8(const Layout& L, const void* packed, const void* xq_buf, int N, void* y, void* acc_out, hipStream_t st);
 int* device_status_word();  // device address of the library's status word on the current device (nullptr on failure)
 int launch_write_descs(const GemvDesc* host, int count, int bits, int group, int has_zero, GemvDesc* dev, hipStream_t st);

@@ -14,10 +14,13 @@
 // and instead of sorting the weights the ACTIVATIONS are stored in that order: the quantizer writes every
 // 32-column group of a token permuted accordingly, so both MFMA operands are plain 16-byte LDS reads.
 //
-// Workgroup = 4 waves = 128 rows x 128 tokens; wave (wm, wn) accumulates 64 x 64 as four 32 x 32 tiles.  Per
+// Two kernels, chosen per call from the grids they give (choose_i8_token_blocks).  The first, for short token
+// ranges and small grids:
+// workgroup = 4 waves = 128 rows x 128 tokens; wave (wm, wn) accumulates 64 x 64 as four 32 x 32 tiles.  Per
 // 64-column stage every wave transposes one 32-weight block of one of the two row blocks into LDS (lane = row),
 // the 128 x 64 bytes of activations go through registers into LDS, one barrier, eight MFMAs per wave.  Two stage
 // buffers: a wave writes stage s + 1 while others still read stage s.
+// The second (mpgemm_i8_wide_kernel, below) keeps the weights out of LDS altogether.
 #include <hip/hip_fp16.h>
 
 #include <mutex>
@@ -317,6 +320,241 @@ __global__ void __launch_bounds__(256) mpgemm_i8_kernel(GemmI8Args a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Wide variant for long token ranges: no weight tile in LDS.  A wave owns 64 rows x 32 TT tokens; it turns the bit
+// planes of its rows into bytes in registers (lane = row) and makes the two MFMA operands of a 32-column step with
+// four v_permlane32_swap (rows 0..31 and rows 32..63, each with the lane halves holding bytes 0..15 and 16..31 of
+// the step).  Only the activations go through LDS, straight from memory, shared by the four waves (256 rows) of
+// the workgroup.  Per MFMA this reads half the LDS bytes of the 128 x 128 kernel and dequantizes each weight once
+// per 32 TT tokens instead of once per 128.
+constexpr int kI8WRing = 4;   // stage buffers of activations in LDS
+constexpr int kI8WSets = 4;   // register sets of bit planes = stages of weight loads in flight
+constexpr int kI8WStageK = 32;
+constexpr int kI8WRows = 256;
+
+template <int TT>
+struct I8Wide {
+    static constexpr int TN = TT * 32;
+    static constexpr int XLoads = (TT + 3) / 4;        // activation loads of a stage per wave (32 token rows each)
+    static constexpr int XBytes = XLoads * 4 * 1024;   // stage buffer: whole loads of all four waves
+    static constexpr int OutRow = kI8WRows * 2 + 16;   // bytes per token of the fp16 output tile in LDS
+    static constexpr int LdsBytes = kI8WRing * XBytes > TN * OutRow ? kI8WRing * XBytes : TN * OutRow;
+};
+
+template <int B, bool HZ, int TT>
+__global__ void __launch_bounds__(256, (TT <= 4 ? 2 : 1)) mpgemm_i8_wide_kernel(GemmI8Args a, int group) {
+    using T = I8Wide<TT>;
+    constexpr int MSZ = HZ ? 4 : 2;
+    constexpr int CH = kKTile / B;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    __shared__ float row_scale[kI8WRows], row_zs[kI8WRows];
+
+    const int MPL = (kKTile / group) * MSZ, TB = B * 1024 + 64 * MPL;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int mt = blockIdx.x / a.n_tiles, nt = blockIdx.x % a.n_tiles;
+    const bool header_ok = header_matches(a.tiles, a.M, a.K, B, group, HZ ? 1 : 0);
+    if (!header_ok && blockIdx.x == 0 && tid == 0) report_header_mismatch(a.status);
+    if (mt >= (header_ok ? a.m_tiles : 0)) return;
+    const int n0 = nt * T::TN;
+    const int k_stages = a.K / kI8WStageK, n_stages = (k_stages + kI8WSets - 1) & ~(kI8WSets - 1);
+    const int r = lane & 31, h = lane >> 5;
+
+    i32x16 acc[2][TT];
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+        for (int nb = 0; nb < TT; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[hb][nb][v] = 0;
+
+    // bit planes of this wave's row block, one 32-weight block per stage
+    const int wrb = mt * 4 + wave;
+    const bool wvalid = wrb < a.n_row_blocks;
+    const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? wrb : 0) * a.n_ktiles * TB;
+    const uint32_t wbytes = wvalid ? (uint32_t)(a.n_ktiles * TB) : 0u;
+    uint32_t plane[kI8WSets][B];
+    auto load_planes = [&](uint32_t (&pl)[B], int t) {
+        const rsrc_t rw = rsrc_of(wsrc, t < k_stages ? wbytes : 0u);
+        const int tile = t >> 2, kb32 = t & 3;
+        const int v = (kb32 * 32) / CH, ksub = ((kb32 * 32) % CH) / 32;
+        const int so = tile * TB + v * 1024 + ksub * B * 4;
+        if constexpr (B == 4) {
+            const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rw, lane * 16, so, 0);
+            pl[0] = w.x; pl[1] = w.y; pl[2] = w.z; pl[3] = w.w;
+        } else if constexpr (B == 2) {
+            const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rw, lane * 16, so, 0);
+            pl[0] = w.x; pl[1] = w.y;
+        } else {
+            pl[0] = __builtin_amdgcn_raw_buffer_load_b32(rw, lane * 16, so, 0);
+        }
+    };
+    // activations: load i of a stage brings 32 token rows x 32 bytes straight into LDS (lane -> row lane / 2, half
+    // lane % 2); wave w issues loads w, w + 4, ...; rows beyond the tile's tokens lie outside the resource (zeros)
+    const int xrows = a.N - n0 < T::TN ? a.N - n0 : T::TN;
+    const int8_t* xsrc = a.xq + (size_t)n0 * a.K;
+    const uint32_t xbytes = (uint32_t)xrows * (uint32_t)a.K;
+    const uint32_t xlane = (uint32_t)(lane >> 1) * (uint32_t)a.K + (uint32_t)(lane & 1) * 16u;
+    const uint32_t x32rows = 32u * (uint32_t)a.K;
+    auto load_x = [&](int t) {
+        const rsrc_t rx = rsrc_of(xsrc, t < k_stages ? xbytes : 0u);
+        uint8_t* dst = smem + (t & (kI8WRing - 1)) * T::XBytes;
+#pragma unroll
+        for (int i = 0; i < T::XLoads; ++i) {
+            const int li = wave + 4 * i;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(dst + li * 1024), 16,
+                                                     xlane + (uint32_t)li * x32rows, t * kI8WStageK, 0, 0);
+        }
+    };
+    const int xoff = r * 32 + h * 16;  // operand of token block nb: token nb * 32 + r, bytes 16 h .. 16 h + 15
+    i32x4 xf[2][TT];
+    auto read_x = [&](int set, const uint8_t* stage) {
+#pragma unroll
+        for (int nb = 0; nb < TT; ++nb) xf[set][nb] = *reinterpret_cast<const i32x4*>(stage + xoff + nb * 1024);
+    };
+    i32x4 wf[2][2];  // [set][rows 0..31 / 32..63]
+    auto operands = [&](int set, const uint32_t (&pl)[B]) {
+        u32x4 lo, hi;
+        codes_to_bytes<B>(pl, lo, hi);
+        u32x4 o0, o1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const u32x2 sw = __builtin_amdgcn_permlane32_swap(lo[e], hi[e], false, false);
+            o0[e] = sw.x;
+            o1[e] = sw.y;
+        }
+        wf[set][0] = __builtin_bit_cast(i32x4, o0);
+        wf[set][1] = __builtin_bit_cast(i32x4, o1);
+    };
+
+    load_x(0);
+    load_x(1);
+#pragma unroll
+    for (int u = 0; u < kI8WSets; ++u) load_planes(plane[u], u);
+    // scale and zero of the tile's rows (the first quantization block of a row stands for the whole row)
+    {
+        const int rb = mt * 4 + (tid >> 6), l = tid & 63;
+        float sc = 0.f, zs = 0.f;
+        if (rb < a.n_row_blocks) {
+            const uint8_t* meta = a.tiles + (size_t)rb * a.n_ktiles * TB + B * 1024 + l * MPL;
+            sc = (float)*reinterpret_cast<const _Float16*>(meta);
+            zs = HZ ? (float)*reinterpret_cast<const _Float16*>(meta + 2) * sc : 0.f;
+        }
+        row_scale[tid] = sc;
+        row_zs[tid] = zs;
+    }
+    operands(0, plane[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    load_x(2);
+    __builtin_amdgcn_sched_barrier(0);
+    load_planes(plane[0], kI8WSets);  // (after the activations of stage 2: the waits of the loop count requests in this order)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_barrier" ::: "memory");
+    read_x(0, smem);
+
+    for (int s0 = 0; s0 < n_stages; s0 += kI8WSets) {
+#pragma unroll
+        for (int u = 0; u < kI8WSets; ++u) {
+            const int s = s0 + u;
+            const uint8_t* nxt = smem + ((s + 1) & (kI8WRing - 1)) * T::XBytes;
+            load_x(s + 3);
+            __builtin_amdgcn_sched_barrier(0);
+            // the MFMAs of stage s; meanwhile the activations and the weight operands of stage s + 1
+            read_x((u + 1) & 1, nxt);
+            operands((u + 1) & 1, plane[(u + 1) % kI8WSets]);
+#pragma unroll
+            for (int nb = 0; nb < TT; ++nb) {
+                acc[0][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[u & 1][0], xf[u & 1][nb], acc[0][nb], 0, 0, 0);
+                acc[1][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[u & 1][1], xf[u & 1][nb], acc[1][nb], 0, 0, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 2 * TT; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+                if (i < TT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            load_planes(plane[(u + 1) % kI8WSets], s + 1 + kI8WSets);
+            __builtin_amdgcn_sched_barrier(0);
+            // the activations of stage s + 2 (requested during stage s - 1) are in before any wave goes on: younger
+            // are the weight request of stage s - 1 and the requests just above
+            asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(T::XLoads + 2) : "memory");
+        }
+    }
+    // requests of stages past the end may still be writing zeros to the ring, which the output tile reuses
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // epilogue: C[i][j] of a 32 x 32 tile: i = row 8 (v / 4) + 4 h + v % 4, j = token lane % 32
+    uint8_t* otile = smem;
+#pragma unroll
+    for (int nb = 0; nb < TT; ++nb) {
+        const int tok = nb * 32 + r, gn = n0 + tok;
+        const bool live = gn < a.N;
+        const float delta = live ? a.absmax[gn] * (1.0f / 127.0f) : 0.f;
+        const float sx = live ? (float)a.sums[gn] : 0.f;
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int row = wave * 64 + hb * 32 + 8 * g4 + 4 * h;
+                float v[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float av = (float)acc[hb][nb][4 * g4 + e];
+                    v[e] = HZ ? delta * fmaf(row_scale[row + e], av, -row_zs[row + e] * sx)
+                              : delta * row_scale[row + e] * fmaf(2.f, av, -sx);
+                }
+                half2_t p0, p1;
+                p0.x = (_Float16)v[0]; p0.y = (_Float16)v[1];
+                p1.x = (_Float16)v[2]; p1.y = (_Float16)v[3];
+                u32x2 w = {__builtin_bit_cast(uint32_t, p0), __builtin_bit_cast(uint32_t, p1)};
+                *reinterpret_cast<u32x2*>(otile + tok * T::OutRow + row * 2) = w;
+                if (a.acc_out && live) {
+                    const int gm = mt * kI8WRows + row;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (gm + e < a.M) a.acc_out[(size_t)gn * a.M + gm + e] = acc[hb][nb][4 * g4 + e];
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int m0 = mt * kI8WRows;
+    const bool fast = (a.M % 8 == 0);  // 16-byte aligned rows of y
+    for (int piece = tid; piece < T::TN * (kI8WRows / 8); piece += 256) {
+        const int n = piece / (kI8WRows / 8), c8 = piece % (kI8WRows / 8);
+        const int gn = n0 + n, gm = m0 + c8 * 8;
+        if (gn >= a.N || gm >= a.M) continue;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(otile + n * T::OutRow + c8 * 16);
+        _Float16* dst = a.y + (size_t)gn * a.M + gm;
+        if (fast && gm + 8 <= a.M) {
+            *reinterpret_cast<u32x4*>(dst) = v;
+        } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+            for (int t = 0; t < 8 && gm + t < a.M; ++t)
+                dst[t] = __builtin_bit_cast(_Float16, (uint16_t)(w[t >> 1] >> (16 * (t & 1))));
+        }
+    }
+}
+
+template <int B, bool HZ, int TT>
+static int launch_i8_wide(GemmI8Args a, int group, hipStream_t st) {
+    static std::once_flag once;
+    static hipError_t attr_rc = hipSuccess;
+    std::call_once(once, [] {
+        attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&mpgemm_i8_wide_kernel<B, HZ, TT>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, I8Wide<TT>::LdsBytes);
+    });
+    if (attr_rc != hipSuccess) return TMAN_ERR_LAUNCH;
+    a.m_tiles = (a.n_row_blocks + 3) / 4;
+    a.n_tiles = (a.N + I8Wide<TT>::TN - 1) / I8Wide<TT>::TN;
+    hipLaunchKernelGGL((mpgemm_i8_wide_kernel<B, HZ, TT>), dim3((unsigned)(a.m_tiles * a.n_tiles)), dim3(256),
+                       I8Wide<TT>::LdsBytes, st, a, group);
+    return launch_status();
+}
+
 template <int B, int GQ, bool HZ>
 static int launch_i8_cfg(GemmI8Args a, hipStream_t st) {
     static std::once_flag once;
@@ -341,6 +579,54 @@ static int launch_i8_group(int group, const GemmI8Args& a, hipStream_t st) {
     }
 }
 
+template <int B, bool HZ>
+static int launch_i8_wide_tokens(int tt, const GemmI8Args& a, int group, hipStream_t st) {
+    switch (tt) {
+        case 3: return launch_i8_wide<B, HZ, 3>(a, group, st);
+        case 4: return launch_i8_wide<B, HZ, 4>(a, group, st);
+        default: return launch_i8_wide<B, HZ, 7>(a, group, st);
+    }
+}
+
+// Which kernel, and for the wide one how many 32-token blocks per workgroup: the choice with the least modelled
+// time.  The model counts rounds of workgroups over the compute units with the time one workgroup took on this
+// chip at K = 4096 (microseconds; alone on its unit / sharing it with a second one, which the 96- and 128-token
+// tiles allow), scaled by K; the 128 x 128 kernel's time grows linearly with its workgroups.  1 = that kernel.
+int choose_i8_token_blocks(int n_row_blocks, int N, int K) {
+    static std::once_flag once;
+    static int n_cu = 256;  // assumed when no device answers
+    std::call_once(once, [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            n_cu = n;
+    });
+    const int forced = current_tiling().i8_token_blocks;
+    if (forced == 1 || forced == 3 || forced == 4 || forced == 7) return forced;
+    const double k = (double)K / 4096.0;
+    const long long old_wgs = (long long)((n_row_blocks + 1) / 2) * ((N + kI8Tokens - 1) / kI8Tokens);
+    double best_cost = (17.0 + 0.08 * (double)old_wgs * 256.0 / n_cu) * k;
+    int best = 1;
+    const int tts[3] = {7, 4, 3};
+    const double alone[3] = {59.0, 40.0, 35.0}, shared[3] = {0.0, 58.0, 52.0};
+    for (int i = 0; i < 3; ++i) {
+        const long long wgs = (long long)((n_row_blocks + 3) / 4) * ((N + 32 * tts[i] - 1) / (32 * tts[i]));
+        double cost;
+        if (tts[i] > 4) {
+            cost = (double)((wgs + n_cu - 1) / n_cu) * alone[i];
+        } else {
+            const long long full = wgs / (2 * n_cu), rem = wgs % (2 * n_cu);
+            cost = (double)full * shared[i] + (rem == 0 ? 0.0 : rem > n_cu ? shared[i] : alone[i]);
+        }
+        cost *= k;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = tts[i];
+        }
+    }
+    return best;
+}
+
 int launch_mpgemm_i8(const Layout& L, const void* packed, const void* xq_buf, int N, void* y, void* acc_out, hipStream_t st) {
     const ActI8Layout al = act_i8_layout(N, L.K);
     const uint8_t* xb = static_cast<const uint8_t*>(xq_buf);
@@ -359,6 +645,13 @@ int launch_mpgemm_i8(const Layout& L, const void* packed, const void* xq_buf, in
     a.m_tiles = a.n_tiles = 0;
     a.status = device_status_word();
     if (!a.status) return TMAN_ERR_LAUNCH;
+    const int tt = choose_i8_token_blocks(L.n_row_blocks, N, L.K);
+    if (tt > 1) {
+        if (L.bits == 1)
+            return L.has_zero ? launch_i8_wide_tokens<1, true>(tt, a, L.group, st) : launch_i8_wide_tokens<1, false>(tt, a, L.group, st);
+        if (L.bits == 2) return launch_i8_wide_tokens<2, true>(tt, a, L.group, st);
+        return launch_i8_wide_tokens<4, true>(tt, a, L.group, st);
+    }
     if (L.bits == 1) return L.has_zero ? launch_i8_group<1, true>(L.group, a, st) : launch_i8_group<1, false>(L.group, a, st);
     if (L.bits == 2) return launch_i8_group<2, true>(L.group, a, st);
     return launch_i8_group<4, true>(L.group, a, st);

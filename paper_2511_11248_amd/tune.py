@@ -66,6 +66,21 @@ def main():
         y = torch.empty((N, spec.M), dtype=torch.float16, device=dev)
         return bench.timed_steps(torch, lambda i: tman.tman_mpgemm(ps, blob, x, N, y, None), 40, 100) * 1e6
 
+    def time_prefill_i8(N):
+        pw = synth.WORKLOADS["prefill_w4g64"]
+        spec = pw.layers[0]
+        ps = tman.Shape(spec.M, spec.K, pw.bits, pw.group, True)
+        q, sc, z = synth.layer_tensors(pw, 0, 0, device=dev)
+        sc = sc[:, :1].expand(-1, spec.K // pw.group).contiguous()  # one scale and zero per row
+        z = z[:, :1].expand(-1, spec.K // pw.group).contiguous()
+        blob = torch.empty(tman.tman_packed_bytes(ps), dtype=torch.uint8, device=dev)
+        tman.tman_pack_weights(ps, q, sc, z, blob)
+        x = torch.from_numpy(synth.activation(pw, 0, 0, N)).to(dev)
+        xq = torch.empty(tman.tman_act_i8_bytes(N, spec.K), dtype=torch.uint8, device=dev)
+        tman.tman_quantize_act_i8(x, N, spec.K, xq)
+        y = torch.empty((N, spec.M), dtype=torch.float16, device=dev)
+        return bench.timed_steps(torch, lambda i: tman.tman_mpgemm_i8(ps, blob, xq, N, y, None), 40, 100) * 1e6
+
     def sweep(title, param, values, measure):
         print(f"\n{title}\n  {param}: time per step (us)", flush=True)
         best = None
@@ -103,6 +118,10 @@ def main():
     for N in (256, 1024, 2048):
         sweep(f"prefill 11008 x 4096 uint4 g64, N = {N}: tile blocks in M per workgroup (0 = the launcher's rule)",
               "prefill_row_blocks", [0, 1, 2, 3, 4, 5], lambda: time_prefill(N))
+    for N in (256, 512, 1024, 2048):
+        sweep(f"int8 prefill 11008 x 4096 uint4 per row, N = {N}: 1 = 128 x 128 tiles, 3 / 4 / 7 = 256 rows x 96 / 128 / 224 "
+              "tokens dequantized in registers (0 = the launcher's rule, 2 does not exist)",
+              "i8_token_blocks", [0, 1, 2, 3, 4, 7], lambda: time_prefill_i8(N))
     print(f"\nsearch took {time.time() - t0:.0f} s")
 
 

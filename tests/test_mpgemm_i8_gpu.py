@@ -72,8 +72,23 @@ SHAPES = [
 ]
 
 
+@pytest.fixture
+def restore_tiling():
+    yield
+    tman.tman_set_tiling(tman.tman_default_tiling())
+
+
+def _force(blocks):
+    t = tman.tman_default_tiling()
+    t.i8_token_blocks = blocks
+    tman.tman_set_tiling(t)
+
+
+# 1: the kernel with 128 x 128 tiles; 3, 4, 7: the kernel that dequantizes in registers, 96 / 128 / 224 tokens per workgroup
+@pytest.mark.parametrize("blocks", [1, 3, 4, 7])
 @pytest.mark.parametrize("M,K,bits,hz,group,N", SHAPES)
-def test_accumulators_are_exact_and_outputs_close(oracle_lib, M, K, bits, hz, group, N):
+def test_accumulators_are_exact_and_outputs_close(oracle_lib, restore_tiling, M, K, bits, hz, group, N, blocks):
+    _force(blocks)
     q, rs, rz, s, z, x = _case(600 + M + K + N, M, K, N, bits, hz, group)
     shape = tman.Shape(M, K, bits, group, hz)
     blob = pack(shape, q, s, z)
@@ -115,3 +130,32 @@ def test_ternary_per_tensor_weights(oracle_lib):
     # and the int8 activations keep the result close to the fp16-activation product (8-bit steps: about 1 %)
     Yf = oracle.matmul(t, s, z, x, 2, group)
     assert np.abs(Y - Yf).max() <= 0.05 * np.sqrt(np.mean(Yf * Yf))
+
+
+def test_every_kernel_gives_the_same_bits_at_full_size(oracle_lib, restore_tiling):
+    """11008 x 4096 uint4 with one scale and zero per row, N = 1000 (a ragged last token tile for every tile width):
+    the kernel chosen for the call against the oracle on sampled whole tokens, and every other kernel against it
+    bit for bit (the integer accumulators are exact and the epilogue is the same arithmetic)."""
+    M, K, bits, group, N = 11008, 4096, 4, 64, 1000
+    q, rs, rz, s, z, x = _case(77, M, K, N, bits, True, group)
+    shape = tman.Shape(M, K, bits, group, True)
+    blob = pack(shape, q, s, z)
+    xbuf = _quantize(x)
+    assert tman.tman_mpgemm_i8_token_blocks(shape, N) in (3, 4, 7)
+    y = torch.full((N, M), float("nan"), dtype=torch.float16, device=dev())
+    tman.tman_mpgemm_i8(shape, blob, xbuf, N, y, None)
+    torch.cuda.synchronize()
+    assert tman.tman_device_status() == 0
+    yh = y.cpu().numpy()
+    assert np.all(np.isfinite(yh.astype(np.float32)))
+    tokens = sorted({0, 95, 96, 127, 128, 223, 224, 255, 256, 671, 672, 895, 896, 959, 960, 991, 992, 999})
+    xq, mx = oracle.quantize_activations_i8(x[tokens])
+    _, Y = oracle.matmul_i8(q, rs, rz, xq, mx, bits)
+    err = oracle.row_relative_error(yh[tokens], Y)
+    assert err.max() <= TOL_I8, f"row-normalised error {err.max():.3e}"
+    for blocks in (1, 3, 4, 7):
+        _force(blocks)
+        y2 = torch.full((N, M), float("nan"), dtype=torch.float16, device=dev())
+        tman.tman_mpgemm_i8(shape, blob, xbuf, N, y2, None)
+        torch.cuda.synchronize()
+        assert np.array_equal(y2.cpu().numpy().view(np.uint16), yh.view(np.uint16)), blocks

@@ -33,6 +33,7 @@ def test_defaults_are_current_and_consistent():
     dict(prefill_row_blocks=5),             # Eq. 4: 4 x (320 x 80 + 256 x 64) bytes exceed 160 KB
     dict(prefill_row_blocks=-1),
     dict(decode_seg_tiles=0), dict(decode_seg_tiles_many=0), dict(small_seg_tiles=0), dict(decode_x_whole_bytes=0),
+    dict(i8_token_blocks=2), dict(i8_token_blocks=8), dict(i8_token_blocks=-1),  # only 0, 1, 3, 4 and 7 exist
 ])
 def test_constraint_violations_are_refused_and_change_nothing(bad):
     with pytest.raises(tman.TmanError) as e:
@@ -57,3 +58,14 @@ def test_tiling_enters_the_plans():
     assert tman.tman_mpgemm_tile_rows(pre, 1024) == 192
     tman.tman_set_tiling(_with(prefill_row_blocks=2))
     assert tman.tman_mpgemm_tile_rows(pre, 1024) == 128
+    # the integer prefill kernel: chosen per call (a short token range: the 128 x 128 kernel; long ones: the kernel that
+    # dequantizes in registers, with the token tile that fills 256 units best), or forced
+    tman.tman_set_tiling(tman.tman_default_tiling())
+    assert tman.tman_mpgemm_i8_token_blocks(pre, 256) == 1
+    assert tman.tman_mpgemm_i8_token_blocks(pre, 1024) in (3, 4, 7)
+    assert tman.tman_mpgemm_i8_token_blocks(tman.Shape(256, 512, 4, 64), 128) == 1
+    assert tman.tman_mpgemm_i8_token_blocks(tman.Shape(256, 500, 4, 64), 128) == 0
+    for forced in (1, 3, 4, 7):
+        tman.tman_set_tiling(_with(i8_token_blocks=forced))
+        assert tman.tman_mpgemm_i8_token_blocks(pre, 1024) == forced
+        assert tman.tman_mpgemm_i8_token_blocks(pre, 5) == forced
