@@ -290,11 +290,13 @@ int tman_mpgemm_i8(const tman_shape_t *shape, const void *packed, const void *xq
                    void *stream);
 
 /*
- * Rows of W (output features) one workgroup of tman_mpgemm's tiled kernel covers for this shape and N: 64, 128, 192 or 256,
+ * Rows of W (output features) one workgroup of tman_mpgemm covers for this shape and N > 32: 64, 128, 192 or 256,
  * chosen so that the workgroups fill the compute units of the current device best (256 units are
- * assumed when no device is present).  Informational; 0 for an invalid shape or N < 1.
+ * assumed when no device is present).  tman_mpgemm_splits_k tells whether the call goes to the kernel whose waves
+ * split K (1) or to the tiled kernel (0).  Informational; 0 / -1 for an invalid shape or N < 1.
  */
 int32_t tman_mpgemm_tile_rows(const tman_shape_t *shape, int32_t N);
+int32_t tman_mpgemm_splits_k(const tman_shape_t *shape, int32_t N);
 /*
  * Which kernel tman_mpgemm_i8 runs for this shape and N, in the terms of tiling.i8_token_blocks: 1 = the kernel with
  * 128 x 128 tiles, 3 / 4 / 7 = the kernel whose workgroups take 256 rows x 96 / 128 / 224 tokens and dequantize in
@@ -343,6 +345,11 @@ int tman_mpgemv_noalloc(const tman_shape_t *shape, const void *packed, const voi
  *   prefill_row_blocks         tile blocks in M per workgroup of the tiled prefill kernel, 1..4 (Eq. 4: four
  *                              stage buffers of rows x 80 + 256 x 64 bytes within 160 KB of LDS), 0 = chosen per
  *                              call from the grid it gives
+ *   prefill_k_split            tman_mpgemm for N > 32: a grid that leaves compute units idle even with one tile block per
+ *                              workgroup goes to a kernel whose four waves split K (each dequantizes its own stages in
+ *                              registers; the partial sums meet in LDS in a fixed order): 0 = there, when K >= 2048,
+ *                              with the tile chosen per call; 1 = never; 2 / 3 = every call, with the 64 rows x 256
+ *                              tokens / 128 rows x 128 tokens tile
  *   i8_token_blocks            tman_mpgemm_i8: 1 = the kernel with 128 x 128 tiles (weights and activations through
  *                              LDS), 3 / 4 / 7 = the kernel whose waves dequantize their own 64 rows in registers and
  *                              share 96 / 128 / 224 tokens of activations through LDS, 0 = chosen per call from the
@@ -363,6 +370,7 @@ typedef struct tman_tiling {
     int32_t prefill_row_blocks;
     int32_t decode_balance;
     int32_t i8_token_blocks;
+    int32_t prefill_k_split;
 } tman_tiling_t;
 int tman_default_tiling(tman_tiling_t *out);
 int tman_get_tiling(tman_tiling_t *out);

@@ -29,7 +29,7 @@ class Tiling(C.Structure):
     """Mirror of ``tman_tiling_t`` (see include/tman.h)."""
     _fields_ = [("decode_seg_tiles", C.c_int32), ("decode_seg_tiles_many", C.c_int32), ("decode_x_seg_tiles", C.c_int32),
                 ("decode_x_long_seg_tiles", C.c_int32), ("decode_x_whole_bytes", C.c_int32), ("small_seg_tiles", C.c_int32),
-                ("prefill_row_blocks", C.c_int32), ("decode_balance", C.c_int32), ("i8_token_blocks", C.c_int32)]
+                ("prefill_row_blocks", C.c_int32), ("decode_balance", C.c_int32), ("i8_token_blocks", C.c_int32), ("prefill_k_split", C.c_int32)]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -123,6 +123,8 @@ def _load():
         L.tman_mpgemm_i8.argtypes = [sp, vp, vp, C.c_int32, vp, vp, vp]
         L.tman_mpgemm_tile_rows.restype = C.c_int32
         L.tman_mpgemm_tile_rows.argtypes = [sp, C.c_int32]
+        L.tman_mpgemm_splits_k.restype = C.c_int32
+        L.tman_mpgemm_splits_k.argtypes = [sp, C.c_int32]
         L.tman_mpgemm_i8_token_blocks.restype = C.c_int32
         L.tman_mpgemm_i8_token_blocks.argtypes = [sp, C.c_int32]
         L.tman_check_packed.restype = C.c_int
@@ -197,6 +199,10 @@ def tman_mpgemm_workspace_bytes(shape: Shape, N: int) -> int:
 
 def tman_mpgemm_tile_rows(shape: Shape, N: int) -> int:
     return int(_load().tman_mpgemm_tile_rows(C.byref(shape.c()), N))
+
+
+def tman_mpgemm_splits_k(shape: Shape, N: int) -> int:
+    return int(_load().tman_mpgemm_splits_k(C.byref(shape.c()), N))
 
 
 def tman_mpgemm_i8_token_blocks(shape: Shape, N: int) -> int:

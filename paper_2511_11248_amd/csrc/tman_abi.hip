@@ -341,6 +341,11 @@ int32_t tman_mpgemm_tile_rows(const tman_shape_t* shape, int32_t N) {
     return kRows * mpgemm_row_blocks_per_workgroup(make_layout(shape), N);
 }
 
+int32_t tman_mpgemm_splits_k(const tman_shape_t* shape, int32_t N) {
+    if (check_shape(shape) != TMAN_OK || N < 1) return -1;
+    return mpgemm_splits_k(make_layout(shape), N);
+}
+
 int32_t tman_mpgemm_i8_token_blocks(const tman_shape_t* shape, int32_t N) {
     if (check_shape(shape) != TMAN_OK || N < 1) return 0;
     const Layout L = make_layout(shape);

@@ -169,5 +169,6 @@ int* device_status_word();  // device address of the library's status word on th
 int launch_write_descs(const GemvDesc* host, int count, int bits, int group, int has_zero, GemvDesc* dev, hipStream_t st);
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace, hipStream_t st);
 int mpgemm_row_blocks_per_workgroup(const Layout& L, int N);
+int mpgemm_splits_k(const Layout& L, int N);
 
 }  // namespace tman

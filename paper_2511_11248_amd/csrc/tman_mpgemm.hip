@@ -22,6 +22,7 @@
 // GPU form of DMA -> vector -> matrix): producer waves keep packed weights four stages ahead in registers
 // and fill a ring of four LDS stage buffers; consumer waves feed v_mfma_f32_32x32x16_f16
 // (fp32 accumulation) from the ring; one barrier per 32-column stage.
+// Grids too small for that kernel (at most one workgroup per compute unit) go to mpgemm_ksplit_kernel, below.
 #include <hip/hip_fp16.h>
 
 #include <mutex>
@@ -435,6 +436,266 @@ __global__ void __launch_bounds__(kThreads, 1) mpgemm_kernel(GemmArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// One row block per workgroup (grids that would otherwise leave compute units idle): 64 rows x 256 tokens, the
+// four waves split K.  Wave w takes the 32-column stages w, w + 4, ... whole: it dequantizes the stage's weights in
+// registers (lane = row; v_permlane32_swap makes the MFMA operands, as in the small-batch kernel), brings the
+// stage's activations into its own LDS buffers and multiplies them with all 256 tokens.  So every weight is still
+// dequantized once per 256 tokens, no weight goes through LDS, a wave reads 0.5 KB of LDS per MFMA instead of
+// 1.5 KB, and the waves never wait for one another until the end, where their four partial tiles meet in LDS
+// (added in wave order: results do not depend on timing).
+// Two shapes of the tile: 64 rows x 256 tokens, or 128 rows x 128 tokens (every wave then dequantizes two row
+// blocks per stage and needs half the activation bytes per MFMA; its activation buffers are half as large, so
+// four instead of two of them fit and the requests run three own stages ahead instead of one).
+constexpr int kKsSets = 4;  // register sets of packed weights = own stages in flight per wave
+template <int RBW, int TT>
+struct KsTile {
+    static constexpr int TN = 32 * TT, TM = 64 * RBW;
+    static constexpr int XBytes = TN * kStageK * 2;           // activations of a stage
+    static constexpr int NBuf = 128 * 1024 / (4 * XBytes);   // activation buffers per wave
+    static constexpr int XLoads = TN / 16;                    // requests per stage (16 token rows each)
+    static constexpr int PartRow = TM * 4 + 16;               // bytes per token of a wave's partial tile in LDS
+    static constexpr int PartBytes = (TN / 2) * PartRow;      // ... of half of its tokens
+    static constexpr int LdsBytes = 4 * NBuf * XBytes > 4 * PartBytes ? 4 * NBuf * XBytes : 4 * PartBytes;
+    static_assert(RBW * TT == 8 && NBuf >= 2 && LdsBytes <= 160 * 1024, "tile of the K-split kernel");
+};
+
+template <int B, int GQ, bool HZ, int RBW, int TT>
+__global__ void __launch_bounds__(256, 1) mpgemm_ksplit_kernel(GemmArgs a) {
+    using T = KsTile<RBW, TT>;
+    constexpr int MSZ = HZ ? 4 : 2;
+    constexpr int TB = B * 1024 + 64 * (kKTile / GQ) * MSZ;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+    const int mt = (slot / a.n_tiles) * kXcds + xcd, nt = slot % a.n_tiles;
+    const bool header_ok = header_matches(a.tiles, a.M, a.K, B, GQ, HZ ? 1 : 0);
+    if (!header_ok && blockIdx.x == 0 && threadIdx.x == 0) report_header_mismatch(a.status);
+    if (mt >= (header_ok ? a.m_tiles : 0)) return;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int n0 = nt * T::TN;
+    const int k_stages = a.K / kStageK;
+    // own stages of this wave: wave, wave + 4, ...; the loop runs whole rounds of kKsSets own stages (a stage past
+    // K has empty sources: zero weights, zero activations)
+    const int n_own = (k_stages + 3) / 4, n_own_pad = (n_own + kKsSets - 1) & ~(kKsSets - 1);
+    const int r = lane & 31, h = lane >> 5;
+
+    float16_t acc[RBW][2][TT];
+#pragma unroll
+    for (int b = 0; b < RBW; ++b)
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+            for (int nb = 0; nb < TT; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[b][hb][nb][v] = 0.f;
+
+    WRegs<B> wr[kKsSets][RBW];
+    auto load_wregs = [&](int set, int i) {  // own stage i = stage 4 i + wave, every row block of the tile
+        const int t = 4 * i + wave;
+#pragma unroll
+        for (int b = 0; b < RBW; ++b) {
+            const int rb = mt * RBW + b;
+            const bool wvalid = rb < a.n_row_blocks;
+            const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? rb : 0) * a.n_ktiles * TB;
+            load_w<B, GQ, HZ>(wr[set][b], make_rsrc(wsrc, t < k_stages && wvalid ? 0x7fffffffu : 0u), t >> 2, t & 3, lane);
+        }
+    };
+    // activations of own stage i go to this wave's buffer i % NBuf
+    const int xrows = a.N - n0 < T::TN ? a.N - n0 : T::TN;
+    const _Float16* xsrc = a.x + (size_t)n0 * a.K;
+    const uint32_t xbytes = (uint32_t)xrows * (uint32_t)a.K * 2u;
+    const uint32_t xlane = ((lane >> 2) * (uint32_t)a.K + ((lane & 3) ^ ((lane >> 4) & 3)) * 8u) * 2u;
+    const uint32_t x16rows = 16u * (uint32_t)a.K * 2u;
+    uint8_t* const xbuf = smem + wave * T::NBuf * T::XBytes;
+    auto load_x = [&](int i) {
+        const int t = 4 * i + wave;
+        const rsrc_t rx = make_rsrc(xsrc, t < k_stages ? xbytes : 0u);
+        uint8_t* dst = xbuf + (i & (T::NBuf - 1)) * T::XBytes;
+#pragma unroll
+        for (int q = 0; q < T::XLoads; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(dst + q * 1024), 16,
+                                                     xlane + (uint32_t)q * x16rows, t * kStageK * 2, 0, 0);
+    };
+    const int xrow = r * (kStageK * 2);
+    const int xchunk[2] = {xrow + ((h ^ ((r >> 2) & 3)) * 16), xrow + (((2 + h) ^ ((r >> 2) & 3)) * 16)};
+    half8_t xf[2][TT];
+    auto read_x = [&](int j, const uint8_t* stage) {
+#pragma unroll
+        for (int nb = 0; nb < TT; ++nb)
+            xf[j][nb] = *reinterpret_cast<const half8_t*>(stage + xchunk[j] + nb * 32 * (kStageK * 2));
+    };
+    half8_t wf[2][RBW][2][2];  // [set][row block][rows 0..31 / 32..63][16-column step]
+    Dequant<B, HZ> dq;
+    auto operands = [&](int set, int b, int j) {
+        const u32x4 pa = dq.piece(2 * j), pb = dq.piece(2 * j + 1);
+        u32x4 lo, hi;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const u32x2 sw = __builtin_amdgcn_permlane32_swap(pa[e], pb[e], false, false);
+            lo[e] = sw.x;
+            hi[e] = sw.y;
+        }
+        wf[set][b][0][j] = __builtin_bit_cast(half8_t, lo);
+        wf[set][b][1][j] = __builtin_bit_cast(half8_t, hi);
+    };
+    auto mfmas = [&](int set, int j) {
+#pragma unroll
+        for (int nb = 0; nb < TT; ++nb)
+#pragma unroll
+            for (int b = 0; b < RBW; ++b) {
+                acc[b][0][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[set][b][0][j], xf[j][nb], acc[b][0][nb], 0, 0, 0);
+                acc[b][1][nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[set][b][1][j], xf[j][nb], acc[b][1][nb], 0, 0, 0);
+            }
+    };
+    // the vector work of a stage in two parts, one beside each 16-column step of the previous stage: with one row
+    // block level 1 / level 2 of it, with two the whole of block 0 / of block 1
+    auto dequant_part = [&](int part, int wset, int oset) {
+        if constexpr (RBW == 1) {
+            if (part == 0) {
+                dq.start(wr[wset][0]);
+                dq.insert();
+            } else {
+                operands(oset, 0, 0);
+                operands(oset, 0, 1);
+            }
+        } else {
+            dq.start(wr[wset][part]);
+            dq.insert();
+            operands(oset, part, 0);
+            operands(oset, part, 1);
+        }
+    };
+
+    // prologue: activations of own stage 0 in LDS and those of own stage 1 requested; weights of own stages 1..4 in
+    // the register sets, own stage 0 dequantized into operand set 0
+    load_x(0);
+#pragma unroll
+    for (int i = 0; i < kKsSets; ++i) load_wregs(i, i);
+    dequant_part(0, 0, 0);
+    dequant_part(1, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int i = 1; i < T::NBuf; ++i) load_x(i);
+    __builtin_amdgcn_sched_barrier(0);
+    load_wregs(0, kKsSets);
+    __builtin_amdgcn_sched_barrier(0);
+    read_x(0, xbuf);
+
+    for (int i0 = 0; i0 < n_own_pad; i0 += kKsSets) {
+#pragma unroll
+        for (int u = 0; u < kKsSets; ++u) {
+            const int i = i0 + u;
+            const uint8_t* cur = xbuf + (i & (T::NBuf - 1)) * T::XBytes;
+            const uint8_t* nxt = xbuf + ((i + 1) & (T::NBuf - 1)) * T::XBytes;
+            // first half: 16-column step 0 of own stage i; meanwhile the activations of step 1 and level 1 of the
+            // next own stage
+            read_x(1, cur);
+            dequant_part(0, (u + 1) % kKsSets, (u + 1) & 1);
+            mfmas(u & 1, 0);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, RBW == 1 ? 3 : 6, 0);
+                if (q < TT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // second half: step 1; meanwhile the rest of the next own stage's vector work
+            dequant_part(1, (u + 1) % kKsSets, (u + 1) & 1);
+            mfmas(u & 1, 1);
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, RBW == 1 ? 5 : 6, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // The buffer of own stage i is free now (its operand reads are consumed): request own stage i + NBuf
+            // into it.  Before the reads that follow, the activations of own stage i + 1 must be in: what was
+            // requested after them is at least the activations of NBuf - 2 stages and one stage's weights (requests
+            // complete in order; older weight requests are long in by then).
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((T::NBuf - 2) * T::XLoads + 2 * RBW) : "memory");
+            load_x(i + T::NBuf);
+            __builtin_amdgcn_sched_barrier(0);
+            load_wregs((u + 1) % kKsSets, i + 1 + kKsSets);
+            __builtin_amdgcn_sched_barrier(0);
+            read_x(0, nxt);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // requests of own stages past the end may still be writing zeros to LDS, which the partial tiles reuse
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // The four partial tiles meet in LDS, half of the tokens at a time: wave w writes its fp32 sums as
+    // [token][row], then thread -> (token, 8 rows) adds the four in wave order and stores fp16.
+    // acc[b][hb][nb][v] is row 64 b + 32 hb + 8 (v / 4) + 4 h + v % 4 for token 32 nb + r.
+    const int m0 = mt * T::TM;
+    const bool fast = (a.M % 8 == 0);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        uint8_t* mine = smem + wave * T::PartBytes;
+#pragma unroll
+        for (int nq = 0; nq < TT / 2; ++nq) {
+            const int nb = half * (TT / 2) + nq;
+#pragma unroll
+            for (int b = 0; b < RBW; ++b)
+#pragma unroll
+                for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        float* dst = reinterpret_cast<float*>(mine + (nq * 32 + r) * T::PartRow + (64 * b + 32 * hb + 8 * g + 4 * h) * 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) dst[e] = acc[b][hb][nb][4 * g + e];
+                    }
+        }
+        __syncthreads();
+        for (int piece = tid; piece < (T::TN / 2) * (T::TM / 8); piece += 256) {
+            const int n = piece / (T::TM / 8), c8 = piece % (T::TM / 8);
+            const int gn = n0 + half * (T::TN / 2) + n, gm = m0 + c8 * 8;
+            float sum[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum[e] = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float* src = reinterpret_cast<const float*>(smem + w * T::PartBytes + n * T::PartRow + c8 * 32);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sum[e] += src[e];
+            }
+            if (gn >= a.N || gm >= a.M) continue;
+            _Float16* dst = a.y + (size_t)gn * a.M + gm;
+            if (fast && gm + 8 <= a.M) {
+                half8_t o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (_Float16)sum[e];
+                *reinterpret_cast<half8_t*>(dst) = o;
+            } else {
+                for (int t = 0; t < 8 && gm + t < a.M; ++t) dst[t] = (_Float16)sum[t];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int B, int GQ, bool HZ, int RBW, int TT>
+static int launch_ksplit(GemmArgs a, hipStream_t st) {
+    using T = KsTile<RBW, TT>;
+    static std::once_flag once;
+    static hipError_t attr_rc = hipSuccess;
+    std::call_once(once, [] {
+        attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&mpgemm_ksplit_kernel<B, GQ, HZ, RBW, TT>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, T::LdsBytes);
+    });
+    if (attr_rc != hipSuccess) return TMAN_ERR_LAUNCH;
+    a.m_tiles = (a.n_row_blocks + RBW - 1) / RBW;
+    a.n_tiles = (a.N + T::TN - 1) / T::TN;
+    const unsigned grid = (unsigned)((a.m_tiles + kXcds - 1) / kXcds * kXcds * a.n_tiles);
+    hipLaunchKernelGGL((mpgemm_ksplit_kernel<B, GQ, HZ, RBW, TT>), dim3(grid), dim3(256), T::LdsBytes, st, a);
+    return launch_status();
+}
+
 template <int B, int GQ, bool HZ, int RB>
 static int launch_tile(GemmArgs a, hipStream_t st) {
     // once per kernel instantiation, also when several host threads make their first call together
@@ -452,10 +713,15 @@ static int launch_tile(GemmArgs a, hipStream_t st) {
     return launch_status();
 }
 
-// Rows per workgroup: the choice that needs the least time, counted as rounds of workgroups over the
-// compute units times rows per workgroup, with a small bonus for larger tiles (fewer operand reads
-// and less dequantization per MFMA).
-static int choose_row_blocks(int n_row_blocks, int N) {
+// Which kernel and tile: 1 .. 4 = the tiled kernel with that many row blocks per workgroup; kSplitWide /
+// kSplitTall = the K-split kernel with 64 rows x 256 tokens / 128 rows x 128 tokens.
+// Tiled kernel: the row blocks that need the least time, counted as rounds of workgroups over the compute units
+// times rows per workgroup, with a small bonus for larger tiles (fewer operand reads and less dequantization per
+// MFMA).  A grid that leaves compute units idle even with one row block per workgroup goes to the K-split kernel
+// (measured 10 - 40 % faster there) unless K is short: the tall tile when the workgroups' activation streams are
+// what limits them (more than 256 tokens, or a full 256 with at least half of the units busy), else the wide one.
+constexpr int kSplitWide = 5, kSplitTall = 6;
+static int choose_tile(int n_row_blocks, int N, int K) {
     static std::once_flag once;
     static int n_cu = 256;  // assumed when no device answers
     std::call_once(once, [] {
@@ -464,12 +730,16 @@ static int choose_row_blocks(int n_row_blocks, int N) {
             hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
             n_cu = n;
     });
-    const int forced = current_tiling().prefill_row_blocks;
+    const tman_tiling_t t = current_tiling();
+    if (t.prefill_k_split == 2) return kSplitWide;
+    if (t.prefill_k_split == 3) return kSplitTall;
+    const int forced = t.prefill_row_blocks;
     if (forced >= 1 && forced <= 4) return forced;
     const int n_tiles = (N + kTN - 1) / kTN;
-    // A grid that leaves compute units idle even with one row block per workgroup: the time of a workgroup
-    // is then set by the chain load -> dequantize -> barrier of its stages, shortest with the smallest tile.
-    if ((long long)n_row_blocks * n_tiles <= n_cu) return 1;
+    if ((long long)n_row_blocks * n_tiles <= n_cu) {
+        if (t.prefill_k_split == 1 || K < 2048) return 1;
+        return N > 256 || (N > 192 && (long long)n_row_blocks * n_tiles * 2 >= n_cu) ? kSplitTall : kSplitWide;
+    }
     const double penalty[5] = {0, 0, 1.10, 1.03, 1.0};
     int best = 4;
     double best_cost = 1e30;
@@ -486,7 +756,9 @@ static int choose_row_blocks(int n_row_blocks, int N) {
 
 template <int B, int GQ, bool HZ>
 static int launch_cfg(const GemmArgs& a, hipStream_t st) {
-    switch (choose_row_blocks(a.n_row_blocks, a.N)) {
+    switch (choose_tile(a.n_row_blocks, a.N, a.K)) {
+        case kSplitWide: return launch_ksplit<B, GQ, HZ, 1, 8>(a, st);
+        case kSplitTall: return launch_ksplit<B, GQ, HZ, 2, 4>(a, st);
         case 1: return launch_tile<B, GQ, HZ, 1>(a, st);
         case 2: return launch_tile<B, GQ, HZ, 2>(a, st);
         case 3: return launch_tile<B, GQ, HZ, 3>(a, st);
@@ -503,7 +775,14 @@ static int launch_group(int group, const GemmArgs& a, hipStream_t st) {
     }
 }
 
-int mpgemm_row_blocks_per_workgroup(const Layout& L, int N) { return choose_row_blocks(L.n_row_blocks, N); }
+int mpgemm_row_blocks_per_workgroup(const Layout& L, int N) {
+    const int c = choose_tile(L.n_row_blocks, N, L.K);
+    return c == kSplitWide ? 1 : c == kSplitTall ? 2 : c;
+}
+int mpgemm_splits_k(const Layout& L, int N) {
+    const int c = choose_tile(L.n_row_blocks, N, L.K);
+    return c == kSplitWide || c == kSplitTall;
+}
 
 int launch_mpgemm(const Layout& L, const void* packed, const void* x, int N, void* y, void* workspace,
                   hipStream_t st) {

@@ -15,6 +15,7 @@
 //                       (not a tile size, but it decides which segment length is best);
 //   prefill_row_blocks  tile blocks in M per prefill workgroup; Eq. 4 reads ring (4) x stage bytes <= 160 KB of
 //                       LDS, which admits at most 4;
+//   prefill_k_split     whether small prefill grids go to the kernel whose waves split K, and with which tile;
 //   i8_token_blocks     which integer-matrix-core prefill kernel runs and how many tokens its workgroup takes.
 // The defaults are the best of the measured sweep in paper_2511_11248_amd/tune.py over the benchmark shapes.
 #include <atomic>
@@ -24,7 +25,7 @@
 
 namespace tman {
 
-static constexpr tman_tiling_t kDefaultTiling = {32, 24, 32, 17, 81920, 43, 0, 1, 0};
+static constexpr tman_tiling_t kDefaultTiling = {32, 24, 32, 17, 81920, 43, 0, 1, 0, 0};
 static std::mutex tiling_mutex;
 static tman_tiling_t tiling_now = kDefaultTiling;
 
@@ -48,6 +49,9 @@ static int check_tiling(const tman_tiling_t& t) {
     if (t.prefill_row_blocks < 0 || t.prefill_row_blocks > 4) return TMAN_ERR_SHAPE;
     const int rb = t.prefill_row_blocks ? t.prefill_row_blocks : 4;
     if (kRing * (rb * kRows * 80 + 256 * 64) > kLdsBytes) return TMAN_ERR_SHAPE;
+    // the prefill kernel whose waves split K: 0 = where it is measured faster, 1 = never, 2 / 3 = always, with its
+    // 64 x 256 / 128 x 128 tile (its LDS, 128 KB of activation buffers or 135 KB of partial tiles, fits for both)
+    if (t.prefill_k_split < 0 || t.prefill_k_split > 3) return TMAN_ERR_SHAPE;
     // the integer prefill kernel: 0 = chosen per call, 1 = the 128 x 128 kernel, 3 / 4 / 7 = the wide kernel with that
     // many 32-token blocks per workgroup (its output tile, tokens x 528 bytes, fits the LDS for all three)
     if (t.i8_token_blocks != 0 && t.i8_token_blocks != 1 && t.i8_token_blocks != 3 && t.i8_token_blocks != 4 &&

@@ -118,6 +118,10 @@ def main():
     for N in (256, 1024, 2048):
         sweep(f"prefill 11008 x 4096 uint4 g64, N = {N}: tile blocks in M per workgroup (0 = the launcher's rule)",
               "prefill_row_blocks", [0, 1, 2, 3, 4, 5], lambda: time_prefill(N))
+    for N in (128, 256):
+        sweep(f"prefill 11008 x 4096 uint4 g64, N = {N}: 1 = the tiled kernel, 2 / 3 = the kernel whose waves split K with its "
+              "64 x 256 / 128 x 128 tile (0 = the launcher's rule)",
+              "prefill_k_split", [0, 1, 2, 3], lambda: time_prefill(N))
     for N in (256, 512, 1024, 2048):
         sweep(f"int8 prefill 11008 x 4096 uint4 per row, N = {N}: 1 = 128 x 128 tiles, 3 / 4 / 7 = 256 rows x 96 / 128 / 224 "
               "tokens dequantized in registers (0 = the launcher's rule, 2 does not exist)",

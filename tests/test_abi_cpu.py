@@ -228,7 +228,12 @@ def test_prefill_tile_rows_query(lib):
     device): a grid of at most one workgroup per unit takes the lowest tile, 512 / 768 / 1024 row blocks fill
     one round with 128 / 192 / 256 rows."""
     assert tman.tman_mpgemm_tile_rows(tman.Shape(256, 512, 4, 64, True), 128) == 64
-    assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 256) == 64
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 256) == 128   # the K-split kernel's tall tile
+    assert tman.tman_mpgemm_splits_k(tman.Shape(11008, 4096, 4, 64, True), 256) == 1
+    assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 128) == 64    # ... its wide tile
+    assert tman.tman_mpgemm_splits_k(tman.Shape(11008, 4096, 4, 64, True), 1024) == 0
+    assert tman.tman_mpgemm_splits_k(tman.Shape(256, 512, 4, 64, True), 128) == 0          # K too short to split
+    assert tman.tman_mpgemm_splits_k(tman.Shape(256, 500, 4, 64, True), 128) == -1
     assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 512) == 128
     assert tman.tman_mpgemm_tile_rows(tman.Shape(32768, 384, 4, 64, True), 200) == 128
     assert tman.tman_mpgemm_tile_rows(tman.Shape(11008, 4096, 4, 64, True), 1024) == 192

@@ -34,10 +34,41 @@ SMALL = [
 ]
 
 
+@pytest.fixture
+def restore_tiling():
+    yield
+    tman.tman_set_tiling(tman.tman_default_tiling())
+
+
+def _k_split(mode):
+    t = tman.tman_default_tiling()
+    t.prefill_k_split = mode
+    tman.tman_set_tiling(t)
+
+
 @pytest.mark.parametrize("M,K,bits,group,hz,N", SMALL)
 def test_small_shapes(oracle_lib, M, K, bits, group, hz, N):
     q, s, z, x = rand_case(3000 + M + K + bits + N, M, K, N, bits, group, hz)
     _check(tman.Shape(M, K, bits, group, hz), q, s, z, x)
+
+
+# the kernel whose waves split K, forced for every call: 2 = 64 rows x 256 tokens, 3 = 128 rows x 128 tokens per workgroup
+K_SPLIT_SHAPES = SMALL + [
+    (130, 4128, 4, 32, True, 300),   # an odd number of row blocks, K = 129 stages (the four waves get 33, 32, 32, 32)
+    (192, 2048, 2, 64, True, 129),
+    (64, 6912, 1, 64, False, 257),
+]
+
+
+@pytest.mark.parametrize("mode", [2, 3])
+@pytest.mark.parametrize("M,K,bits,group,hz,N", K_SPLIT_SHAPES)
+def test_k_split_kernel_on_small_shapes(oracle_lib, restore_tiling, M, K, bits, group, hz, N, mode):
+    _k_split(mode)
+    q, s, z, x = rand_case(3300 + M + K + bits + N, M, K, N, bits, group, hz)
+    shape = tman.Shape(M, K, bits, group, hz)
+    assert tman.tman_mpgemm_splits_k(shape, max(N, 33)) == 1
+    assert tman.tman_mpgemm_tile_rows(shape, max(N, 33)) == (64 if mode == 2 else 128)
+    _check(shape, q, s, z, x)
 
 
 def test_identity_activations_return_dequantized_weights(oracle_lib):
@@ -75,10 +106,33 @@ def test_full_size_prefill_sampled_tokens(oracle_lib, N):
     q, s, z = synth.layer_tensors(w, 0, 0)
     x = synth.activation(w, 0, 0, N)
     shape = tman.Shape(spec.M, spec.K, w.bits, w.group, True)
+    # 172 workgroups of one tile block at N = 256: the call goes to the kernel whose waves split K
+    assert tman.tman_mpgemm_splits_k(shape, N) == (1 if N == 256 else 0)
     y = mpgemm(shape, pack(shape, q, s, z), x)
     assert np.all(np.isfinite(y.astype(np.float32)))
     rng = np.random.default_rng(N)
     rows = sorted(set([0, 1, 127, 128, N // 2, N - 129, N - 128, N - 1]) | set(rng.integers(0, N, 16).tolist()))
+    Y = oracle.matmul(q, s, z, x[rows], w.bits, w.group)
+    err = oracle.row_relative_error(y[rows], Y)
+    assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_full_size_256_tokens_through_every_kernel(oracle_lib, restore_tiling, mode):
+    """11008 x 4096 uint4 g64, N = 256 (the grid where the three kernels compete): the tiled kernel with one tile
+    block per workgroup (1) and both tiles of the K-split kernel (2, 3), 20 whole tokens each against the oracle."""
+    _k_split(mode)
+    N = 256
+    w = synth.WORKLOADS["prefill_w4g64"]
+    spec = w.layers[0]
+    q, s, z = synth.layer_tensors(w, 0, 0)
+    x = synth.activation(w, 0, 0, N)
+    shape = tman.Shape(spec.M, spec.K, w.bits, w.group, True)
+    assert tman.tman_mpgemm_splits_k(shape, N) == (0 if mode == 1 else 1)
+    y = mpgemm(shape, pack(shape, q, s, z), x)
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    rng = np.random.default_rng(mode)
+    rows = sorted(set([0, 31, 32, 63, 64, 127, 128, 255]) | set(rng.integers(0, N, 12).tolist()))
     Y = oracle.matmul(q, s, z, x[rows], w.bits, w.group)
     err = oracle.row_relative_error(y[rows], Y)
     assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
@@ -121,15 +175,17 @@ def test_every_tile_height(oracle_lib, M, rows):
     assert err.max() <= TOL, f"row-normalised error {err.max():.3e}"
 
 
+@pytest.mark.parametrize("mode", [0, 2, 3])
 @pytest.mark.parametrize("poison", [float("nan"), float("inf")])
 @pytest.mark.parametrize("M,K,bits,group,N", [(70, 160, 4, 32, 300), (200, 1056, 2, 32, 513), (64, 96, 1, 32, 7)])
-def test_activations_and_outputs_stay_inside_their_buffers(oracle_lib, poison, M, K, bits, group, N):
+def test_activations_and_outputs_stay_inside_their_buffers(oracle_lib, restore_tiling, poison, M, K, bits, group, N, mode):
     """X and Y are slices of tensors filled with NaN / Inf; the last token tile is ragged (N % 256 != 0) and K
     is not a multiple of the 128-column tile.  A read beyond X would reach the result as NaN, a write beyond Y
-    would overwrite the filler."""
+    would overwrite the filler.  For the tiled kernel and both tiles of the K-split kernel."""
     import torch
     from gpu_helpers import dev
 
+    _k_split(mode)
     hz = bits != 1
     q, s, z, x = rand_case(4000 + M + K + N, M, K, N, bits, group, hz)
     shape = tman.Shape(M, K, bits, group, hz)

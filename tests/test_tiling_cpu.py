@@ -34,6 +34,7 @@ def test_defaults_are_current_and_consistent():
     dict(prefill_row_blocks=-1),
     dict(decode_seg_tiles=0), dict(decode_seg_tiles_many=0), dict(small_seg_tiles=0), dict(decode_x_whole_bytes=0),
     dict(i8_token_blocks=2), dict(i8_token_blocks=8), dict(i8_token_blocks=-1),  # only 0, 1, 3, 4 and 7 exist
+    dict(prefill_k_split=4), dict(prefill_k_split=-1),
 ])
 def test_constraint_violations_are_refused_and_change_nothing(bad):
     with pytest.raises(tman.TmanError) as e:
@@ -58,6 +59,16 @@ def test_tiling_enters_the_plans():
     assert tman.tman_mpgemm_tile_rows(pre, 1024) == 192
     tman.tman_set_tiling(_with(prefill_row_blocks=2))
     assert tman.tman_mpgemm_tile_rows(pre, 1024) == 128
+    # small grids go to the kernel whose waves split K, unless told otherwise
+    tman.tman_set_tiling(tman.tman_default_tiling())
+    assert (tman.tman_mpgemm_splits_k(pre, 256), tman.tman_mpgemm_tile_rows(pre, 256)) == (1, 128)
+    assert (tman.tman_mpgemm_splits_k(pre, 100), tman.tman_mpgemm_tile_rows(pre, 100)) == (1, 64)
+    tman.tman_set_tiling(_with(prefill_k_split=1))
+    assert (tman.tman_mpgemm_splits_k(pre, 256), tman.tman_mpgemm_tile_rows(pre, 256)) == (0, 64)
+    tman.tman_set_tiling(_with(prefill_k_split=2))
+    assert (tman.tman_mpgemm_splits_k(pre, 4096), tman.tman_mpgemm_tile_rows(pre, 4096)) == (1, 64)
+    tman.tman_set_tiling(_with(prefill_k_split=3))
+    assert (tman.tman_mpgemm_splits_k(pre, 4096), tman.tman_mpgemm_tile_rows(pre, 4096)) == (1, 128)
     # the integer prefill kernel: chosen per call (a short token range: the 128 x 128 kernel; long ones: the kernel that
     # dequantizes in registers, with the token tile that fills 256 units best), or forced
     tman.tman_set_tiling(tman.tman_default_tiling())

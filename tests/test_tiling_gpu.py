@@ -23,6 +23,7 @@ def restore():
          prefill_row_blocks=4),
     dict(decode_x_whole_bytes=4096, prefill_row_blocks=2),
     dict(decode_x_long_seg_tiles=32, prefill_row_blocks=3),
+    dict(prefill_k_split=2), dict(prefill_k_split=3, i8_token_blocks=3),
 ])
 def test_every_kernel_under_other_tilings(oracle_lib, setting):
     t = tman.tman_default_tiling()
