@@ -300,7 +300,7 @@ int32_t tman_mpgemm_splits_k(const tman_shape_t *shape, int32_t N);
 /*
  * Which kernel tman_mpgemm_i8 runs for this shape and N, in the terms of tiling.i8_token_blocks: 1 = the kernel with
  * 128 x 128 tiles, 3 / 4 / 7 = the kernel whose workgroups take 256 rows x 96 / 128 / 224 tokens and dequantize in
- * registers.  The choice models the time of the grids they give on the current device (256 units are assumed when
+ * registers, 9 = the kernel whose waves split K.  The choice models the time of the grids they give on the current device (256 units are assumed when
  * no device is present); a non-zero tiling.i8_token_blocks overrides it.  Informational; 0 for an invalid shape or
  * N < 1.
  */
@@ -352,8 +352,9 @@ int tman_mpgemv_noalloc(const tman_shape_t *shape, const void *packed, const voi
  *                              tokens / 128 rows x 128 tokens tile
  *   i8_token_blocks            tman_mpgemm_i8: 1 = the kernel with 128 x 128 tiles (weights and activations through
  *                              LDS), 3 / 4 / 7 = the kernel whose waves dequantize their own 64 rows in registers and
- *                              share 96 / 128 / 224 tokens of activations through LDS, 0 = chosen per call from the
- *                              grids they give
+ *                              share 96 / 128 / 224 tokens of activations through LDS, 9 = the kernel whose four waves
+ *                              split K (128 rows x 128 tokens per workgroup, for small grids), 0 = chosen per call
+ *                              from the grids they give
  * tman_default_tiling gives the built-in values (the best of the measured sweep paper_2511_11248_amd/tune.py
  * makes on the device), tman_get_tiling the current ones; tman_set_tiling checks the constraints
  * (TMAN_ERR_SHAPE if violated) and makes the values current for all later calls of the process.  The tiling

@@ -14,13 +14,13 @@
 // and instead of sorting the weights the ACTIVATIONS are stored in that order: the quantizer writes every
 // 32-column group of a token permuted accordingly, so both MFMA operands are plain 16-byte LDS reads.
 //
-// Two kernels, chosen per call from the grids they give (choose_i8_token_blocks).  The first, for short token
-// ranges and small grids:
+// Three kernels, chosen per call from the grids they give (choose_i8_token_blocks).  The first:
 // workgroup = 4 waves = 128 rows x 128 tokens; wave (wm, wn) accumulates 64 x 64 as four 32 x 32 tiles.  Per
 // 64-column stage every wave transposes one 32-weight block of one of the two row blocks into LDS (lane = row),
 // the 128 x 64 bytes of activations go through registers into LDS, one barrier, eight MFMAs per wave.  Two stage
 // buffers: a wave writes stage s + 1 while others still read stage s.
-// The second (mpgemm_i8_wide_kernel, below) keeps the weights out of LDS altogether.
+// The second (mpgemm_i8_wide_kernel, below) keeps the weights out of LDS altogether; in the third
+// (mpgemm_i8_ksplit_kernel) the waves of a workgroup also split K, for grids too small for the other two.
 #include <hip/hip_fp16.h>
 
 #include <mutex>
@@ -29,6 +29,7 @@
 
 namespace tman {
 
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
@@ -555,6 +556,263 @@ static int launch_i8_wide(GemmI8Args a, int group, hipStream_t st) {
     return launch_status();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Third kernel, for grids that leave compute units idle even with 64-row workgroups: the four waves of a workgroup
+// split K.  Wave w takes the 32-column stages w, w + 4, ... whole: bit planes -> bytes in registers -> operands
+// by v_permlane32_swap (as in the wide kernel), the stage's activations into LDS buffers of its own, MFMAs with all
+// tokens of the tile; no wave waits for another until the end, where the four partial integer tiles are added in
+// LDS (integers: the result does not depend on the grouping, so every kernel of this file gives the same bits).
+// Tile: 128 rows x 128 tokens (two row blocks per wave); the 64 x 256 tile the template also allows was slower
+// everywhere here, where the dequantization is cheap and the activation stream is what a wave waits for.
+constexpr int kI8KsSets = 4;  // register sets of bit planes = own stages in flight per wave
+
+template <int RBW, int TT>
+struct I8KsTile {
+    static constexpr int TN = 32 * TT, TM = 64 * RBW;
+    static constexpr int XBytes = TN * kI8WStageK;            // activations of a stage, 32 bytes per token
+    static constexpr int NBuf = 4;                             // activation buffers per wave
+    static constexpr int XLoads = TN / 32;                     // requests per stage (32 token rows each)
+    static constexpr int PartRow = TM * 4 + 16;                // bytes per token of a wave's partial tile in LDS
+    static constexpr int PartBytes = (TN / 2) * PartRow;       // ... of half of its tokens
+    static constexpr int LdsBytes = 4 * NBuf * XBytes > 4 * PartBytes ? 4 * NBuf * XBytes : 4 * PartBytes;
+    static_assert(RBW * TT == 8 && LdsBytes + 2 * TM * 4 <= 160 * 1024, "tile of the K-split kernel");
+};
+
+template <int B, bool HZ, int RBW, int TT>
+__global__ void __launch_bounds__(256, 1) mpgemm_i8_ksplit_kernel(GemmI8Args a, int group) {
+    using T = I8KsTile<RBW, TT>;
+    constexpr int MSZ = HZ ? 4 : 2;
+    constexpr int CH = kKTile / B;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    __shared__ float row_scale[T::TM], row_zs[T::TM];
+
+    const int MPL = (kKTile / group) * MSZ, TB = B * 1024 + 64 * MPL;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int mt = blockIdx.x / a.n_tiles, nt = blockIdx.x % a.n_tiles;
+    const bool header_ok = header_matches(a.tiles, a.M, a.K, B, group, HZ ? 1 : 0);
+    if (!header_ok && blockIdx.x == 0 && tid == 0) report_header_mismatch(a.status);
+    if (mt >= (header_ok ? a.m_tiles : 0)) return;
+    const int n0 = nt * T::TN;
+    const int k_stages = a.K / kI8WStageK;
+    const int n_own = (k_stages + 3) / 4, n_own_pad = (n_own + kI8KsSets - 1) & ~(kI8KsSets - 1);
+    const int r = lane & 31, h = lane >> 5;
+
+    i32x16 acc[RBW][2][TT];
+#pragma unroll
+    for (int b = 0; b < RBW; ++b)
+#pragma unroll
+        for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+            for (int nb = 0; nb < TT; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[b][hb][nb][v] = 0;
+
+    uint32_t plane[kI8KsSets][RBW][B];
+    auto load_planes = [&](int set, int i) {  // own stage i = stage 4 i + wave, every row block of the tile
+        const int t = 4 * i + wave;
+        const int tile = t >> 2, kb32 = t & 3;
+        const int v = (kb32 * 32) / CH, ksub = ((kb32 * 32) % CH) / 32;
+        const int so = tile * TB + v * 1024 + ksub * B * 4;
+#pragma unroll
+        for (int b = 0; b < RBW; ++b) {
+            const int rb = mt * RBW + b;
+            const bool wvalid = rb < a.n_row_blocks;
+            const uint8_t* wsrc = a.tiles + (size_t)(wvalid ? rb : 0) * a.n_ktiles * TB;
+            const rsrc_t rw = rsrc_of(wsrc, t < k_stages && wvalid ? (uint32_t)(a.n_ktiles * TB) : 0u);
+            uint32_t (&pl)[B] = plane[set][b];
+            if constexpr (B == 4) {
+                const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rw, lane * 16, so, 0);
+                pl[0] = w.x; pl[1] = w.y; pl[2] = w.z; pl[3] = w.w;
+            } else if constexpr (B == 2) {
+                const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rw, lane * 16, so, 0);
+                pl[0] = w.x; pl[1] = w.y;
+            } else {
+                pl[0] = __builtin_amdgcn_raw_buffer_load_b32(rw, lane * 16, so, 0);
+            }
+        }
+    };
+    // activations of own stage i go to this wave's buffer i % NBuf: lane -> token row lane / 2, half lane % 2
+    const int xrows = a.N - n0 < T::TN ? a.N - n0 : T::TN;
+    const int8_t* xsrc = a.xq + (size_t)n0 * a.K;
+    const uint32_t xbytes = (uint32_t)xrows * (uint32_t)a.K;
+    const uint32_t xlane = (uint32_t)(lane >> 1) * (uint32_t)a.K + (uint32_t)(lane & 1) * 16u;
+    const uint32_t x32rows = 32u * (uint32_t)a.K;
+    uint8_t* const xbuf = smem + wave * T::NBuf * T::XBytes;
+    auto load_x = [&](int i) {
+        const int t = 4 * i + wave;
+        const rsrc_t rx = rsrc_of(xsrc, t < k_stages ? xbytes : 0u);
+        uint8_t* dst = xbuf + (i & (T::NBuf - 1)) * T::XBytes;
+#pragma unroll
+        for (int q = 0; q < T::XLoads; ++q)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(dst + q * 1024), 16,
+                                                     xlane + (uint32_t)q * x32rows, t * kI8WStageK, 0, 0);
+    };
+    const int xoff = r * 32 + h * 16;
+    i32x4 xf[2][TT];
+    auto read_x = [&](int set, const uint8_t* stage) {
+#pragma unroll
+        for (int nb = 0; nb < TT; ++nb) xf[set][nb] = *reinterpret_cast<const i32x4*>(stage + xoff + nb * 1024);
+    };
+    i32x4 wf[2][RBW][2];  // [set][row block][rows 0..31 / 32..63]
+    auto operands = [&](int set, int wset) {
+#pragma unroll
+        for (int b = 0; b < RBW; ++b) {
+            u32x4 lo, hi;
+            codes_to_bytes<B>(plane[wset][b], lo, hi);
+            u32x4 o0, o1;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const u32x2 sw = __builtin_amdgcn_permlane32_swap(lo[e], hi[e], false, false);
+                o0[e] = sw.x;
+                o1[e] = sw.y;
+            }
+            wf[set][b][0] = __builtin_bit_cast(i32x4, o0);
+            wf[set][b][1] = __builtin_bit_cast(i32x4, o1);
+        }
+    };
+
+    load_x(0);
+#pragma unroll
+    for (int i = 0; i < kI8KsSets; ++i) load_planes(i, i);
+    // scale and zero of the tile's rows (the first quantization block of a row stands for the whole row)
+    if (tid < T::TM) {
+        const int rb = mt * RBW + (tid >> 6), l = tid & 63;
+        float sc = 0.f, zs = 0.f;
+        if (rb < a.n_row_blocks) {
+            const uint8_t* meta = a.tiles + (size_t)rb * a.n_ktiles * TB + B * 1024 + l * MPL;
+            sc = (float)*reinterpret_cast<const _Float16*>(meta);
+            zs = HZ ? (float)*reinterpret_cast<const _Float16*>(meta + 2) * sc : 0.f;
+        }
+        row_scale[tid] = sc;
+        row_zs[tid] = zs;
+    }
+    operands(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int i = 1; i < T::NBuf; ++i) load_x(i);
+    __builtin_amdgcn_sched_barrier(0);
+    load_planes(0, kI8KsSets);
+    __builtin_amdgcn_sched_barrier(0);
+    read_x(0, xbuf);
+
+    for (int i0 = 0; i0 < n_own_pad; i0 += kI8KsSets) {
+#pragma unroll
+        for (int u = 0; u < kI8KsSets; ++u) {
+            const int i = i0 + u;
+            const uint8_t* nxt = xbuf + ((i + 1) & (T::NBuf - 1)) * T::XBytes;
+            // the MFMAs of own stage i; meanwhile the weight operands of own stage i + 1
+            operands((u + 1) & 1, (u + 1) % kI8KsSets);
+#pragma unroll
+            for (int nb = 0; nb < TT; ++nb)
+#pragma unroll
+                for (int b = 0; b < RBW; ++b) {
+                    acc[b][0][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[u & 1][b][0], xf[u & 1][nb], acc[b][0][nb], 0, 0, 0);
+                    acc[b][1][nb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[u & 1][b][1], xf[u & 1][nb], acc[b][1][nb], 0, 0, 0);
+                }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, RBW == 1 ? 2 : 4, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // The buffer of own stage i is free now: request own stage i + NBuf into it.  Before the reads that
+            // follow, the activations of own stage i + 1 must be in: what was requested after them is at least the
+            // activations of NBuf - 2 stages and one stage's bit planes (requests complete in order).
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((T::NBuf - 2) * T::XLoads + RBW) : "memory");
+            load_x(i + T::NBuf);
+            __builtin_amdgcn_sched_barrier(0);
+            load_planes((u + 1) % kI8KsSets, i + 1 + kI8KsSets);
+            __builtin_amdgcn_sched_barrier(0);
+            read_x((u + 1) & 1, nxt);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // requests of own stages past the end may still be writing zeros to LDS, which the partial tiles reuse
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // The four partial tiles meet in LDS, half of the tokens at a time: wave w writes its int32 sums as
+    // [token][row], then thread -> (token, 8 rows) adds the four, scales and stores fp16.
+    // acc[b][hb][nb][v] is row 64 b + 32 hb + 8 (v / 4) + 4 h + v % 4 for token 32 nb + r.
+    const int m0 = mt * T::TM;
+    const bool fast = (a.M % 8 == 0);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+        uint8_t* mine = smem + wave * T::PartBytes;
+#pragma unroll
+        for (int nq = 0; nq < TT / 2; ++nq) {
+            const int nb = half * (TT / 2) + nq;
+#pragma unroll
+            for (int b = 0; b < RBW; ++b)
+#pragma unroll
+                for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        int32_t* dst = reinterpret_cast<int32_t*>(mine + (nq * 32 + r) * T::PartRow + (64 * b + 32 * hb + 8 * g + 4 * h) * 4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) dst[e] = acc[b][hb][nb][4 * g + e];
+                    }
+        }
+        __syncthreads();
+        for (int piece = tid; piece < (T::TN / 2) * (T::TM / 8); piece += 256) {
+            const int n = piece / (T::TM / 8), c8 = piece % (T::TM / 8);
+            const int gn = n0 + half * (T::TN / 2) + n, gm = m0 + c8 * 8;
+            int32_t sum[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum[e] = 0;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const int32_t* src = reinterpret_cast<const int32_t*>(smem + w * T::PartBytes + n * T::PartRow + c8 * 32);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sum[e] += src[e];
+            }
+            if (gn >= a.N || gm >= a.M) continue;
+            const float delta = a.absmax[gn] * (1.0f / 127.0f);
+            const float sx = (float)a.sums[gn];
+            _Float16 o[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float av = (float)sum[e];
+                const int row = c8 * 8 + e;
+                o[e] = (_Float16)(HZ ? delta * fmaf(row_scale[row], av, -row_zs[row] * sx)
+                                     : delta * row_scale[row] * fmaf(2.f, av, -sx));
+            }
+            _Float16* dst = a.y + (size_t)gn * a.M + gm;
+            if (fast && gm + 8 <= a.M) {
+                half8_t v;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = o[e];
+                *reinterpret_cast<half8_t*>(dst) = v;
+            } else {
+                for (int t = 0; t < 8 && gm + t < a.M; ++t) dst[t] = o[t];
+            }
+            if (a.acc_out) {
+                for (int t = 0; t < 8 && gm + t < a.M; ++t) a.acc_out[(size_t)gn * a.M + gm + t] = sum[t];
+            }
+        }
+        __syncthreads();
+    }
+}
+
+template <int B, bool HZ, int RBW, int TT>
+static int launch_i8_ksplit(GemmI8Args a, int group, hipStream_t st) {
+    using T = I8KsTile<RBW, TT>;
+    static std::once_flag once;
+    static hipError_t attr_rc = hipSuccess;
+    std::call_once(once, [] {
+        attr_rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&mpgemm_i8_ksplit_kernel<B, HZ, RBW, TT>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, T::LdsBytes);
+    });
+    if (attr_rc != hipSuccess) return TMAN_ERR_LAUNCH;
+    a.m_tiles = (a.n_row_blocks + RBW - 1) / RBW;
+    a.n_tiles = (a.N + T::TN - 1) / T::TN;
+    hipLaunchKernelGGL((mpgemm_i8_ksplit_kernel<B, HZ, RBW, TT>), dim3((unsigned)(a.m_tiles * a.n_tiles)), dim3(256),
+                       T::LdsBytes, st, a, group);
+    return launch_status();
+}
+
 template <int B, int GQ, bool HZ>
 static int launch_i8_cfg(GemmI8Args a, hipStream_t st) {
     static std::once_flag once;
@@ -584,6 +842,7 @@ static int launch_i8_wide_tokens(int tt, const GemmI8Args& a, int group, hipStre
     switch (tt) {
         case 3: return launch_i8_wide<B, HZ, 3>(a, group, st);
         case 4: return launch_i8_wide<B, HZ, 4>(a, group, st);
+        case 9: return launch_i8_ksplit<B, HZ, 2, 4>(a, group, st);
         default: return launch_i8_wide<B, HZ, 7>(a, group, st);
     }
 }
@@ -591,7 +850,8 @@ static int launch_i8_wide_tokens(int tt, const GemmI8Args& a, int group, hipStre
 // Which kernel, and for the wide one how many 32-token blocks per workgroup: the choice with the least modelled
 // time.  The model counts rounds of workgroups over the compute units with the time one workgroup took on this
 // chip at K = 4096 (microseconds; alone on its unit / sharing it with a second one, which the 96- and 128-token
-// tiles allow), scaled by K; the 128 x 128 kernel's time grows linearly with its workgroups.  1 = that kernel.
+// tiles allow), scaled by K; the 128 x 128 kernel's time grows linearly with its workgroups.  1 = that kernel,
+// 3 / 4 / 7 = the wide kernel with that many 32-token blocks, 9 = the kernel whose waves split K.
 int choose_i8_token_blocks(int n_row_blocks, int N, int K) {
     static std::once_flag once;
     static int n_cu = 256;  // assumed when no device answers
@@ -602,7 +862,7 @@ int choose_i8_token_blocks(int n_row_blocks, int N, int K) {
             n_cu = n;
     });
     const int forced = current_tiling().i8_token_blocks;
-    if (forced == 1 || forced == 3 || forced == 4 || forced == 7) return forced;
+    if (forced == 1 || forced == 3 || forced == 4 || forced == 7 || forced == 9) return forced;
     const double k = (double)K / 4096.0;
     const long long old_wgs = (long long)((n_row_blocks + 1) / 2) * ((N + kI8Tokens - 1) / kI8Tokens);
     double best_cost = (17.0 + 0.08 * (double)old_wgs * 256.0 / n_cu) * k;
@@ -622,6 +882,17 @@ int choose_i8_token_blocks(int n_row_blocks, int N, int K) {
         if (cost < best_cost) {
             best_cost = cost;
             best = tts[i];
+        }
+    }
+    // the kernel whose waves split K (128 rows x 128 tokens, one workgroup per unit): 19 us per round on an almost
+    // empty chip, 25 when every unit streams activations
+    if (K >= 2048) {
+        const long long wgs = (long long)((n_row_blocks + 1) / 2) * ((N + 127) / 128);
+        const double fill = wgs >= n_cu ? 1.0 : (double)wgs / n_cu;
+        const double cost = (double)((wgs + n_cu - 1) / n_cu) * (19.0 + 6.0 * fill) * k;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = 9;
         }
     }
     return best;

@@ -53,9 +53,10 @@ static int check_tiling(const tman_tiling_t& t) {
     // 64 x 256 / 128 x 128 tile (its LDS, 128 KB of activation buffers or 135 KB of partial tiles, fits for both)
     if (t.prefill_k_split < 0 || t.prefill_k_split > 3) return TMAN_ERR_SHAPE;
     // the integer prefill kernel: 0 = chosen per call, 1 = the 128 x 128 kernel, 3 / 4 / 7 = the wide kernel with that
-    // many 32-token blocks per workgroup (its output tile, tokens x 528 bytes, fits the LDS for all three)
+    // many 32-token blocks per workgroup (its output tile, tokens x 528 bytes, fits the LDS for all three), 9 = the
+    // kernel whose waves split K
     if (t.i8_token_blocks != 0 && t.i8_token_blocks != 1 && t.i8_token_blocks != 3 && t.i8_token_blocks != 4 &&
-        t.i8_token_blocks != 7)
+        t.i8_token_blocks != 7 && t.i8_token_blocks != 9)
         return TMAN_ERR_SHAPE;
     return TMAN_OK;
 }

@@ -124,8 +124,8 @@ def main():
               "prefill_k_split", [0, 1, 2, 3], lambda: time_prefill(N))
     for N in (256, 512, 1024, 2048):
         sweep(f"int8 prefill 11008 x 4096 uint4 per row, N = {N}: 1 = 128 x 128 tiles, 3 / 4 / 7 = 256 rows x 96 / 128 / 224 "
-              "tokens dequantized in registers (0 = the launcher's rule, 2 does not exist)",
-              "i8_token_blocks", [0, 1, 2, 3, 4, 7], lambda: time_prefill_i8(N))
+              "tokens dequantized in registers, 9 = waves split K (0 = the launcher's rule, 2 does not exist)",
+              "i8_token_blocks", [0, 1, 2, 3, 4, 7, 9], lambda: time_prefill_i8(N))
     print(f"\nsearch took {time.time() - t0:.0f} s")
 
 

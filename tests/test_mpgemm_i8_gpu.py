@@ -84,8 +84,9 @@ def _force(blocks):
     tman.tman_set_tiling(t)
 
 
-# 1: the kernel with 128 x 128 tiles; 3, 4, 7: the kernel that dequantizes in registers, 96 / 128 / 224 tokens per workgroup
-@pytest.mark.parametrize("blocks", [1, 3, 4, 7])
+# 1: the kernel with 128 x 128 tiles; 3, 4, 7: the kernel that dequantizes in registers, 96 / 128 / 224 tokens per workgroup;
+# 9: the kernel whose waves split K, 128 rows x 128 tokens per workgroup
+@pytest.mark.parametrize("blocks", [1, 3, 4, 7, 9])
 @pytest.mark.parametrize("M,K,bits,hz,group,N", SHAPES)
 def test_accumulators_are_exact_and_outputs_close(oracle_lib, restore_tiling, M, K, bits, hz, group, N, blocks):
     _force(blocks)
@@ -153,7 +154,7 @@ def test_every_kernel_gives_the_same_bits_at_full_size(oracle_lib, restore_tilin
     _, Y = oracle.matmul_i8(q, rs, rz, xq, mx, bits)
     err = oracle.row_relative_error(yh[tokens], Y)
     assert err.max() <= TOL_I8, f"row-normalised error {err.max():.3e}"
-    for blocks in (1, 3, 4, 7):
+    for blocks in (1, 3, 4, 7, 9):
         _force(blocks)
         y2 = torch.full((N, M), float("nan"), dtype=torch.float16, device=dev())
         tman.tman_mpgemm_i8(shape, blob, xbuf, N, y2, None)

@@ -33,7 +33,7 @@ def test_defaults_are_current_and_consistent():
     dict(prefill_row_blocks=5),             # Eq. 4: 4 x (320 x 80 + 256 x 64) bytes exceed 160 KB
     dict(prefill_row_blocks=-1),
     dict(decode_seg_tiles=0), dict(decode_seg_tiles_many=0), dict(small_seg_tiles=0), dict(decode_x_whole_bytes=0),
-    dict(i8_token_blocks=2), dict(i8_token_blocks=8), dict(i8_token_blocks=-1),  # only 0, 1, 3, 4 and 7 exist
+    dict(i8_token_blocks=2), dict(i8_token_blocks=8), dict(i8_token_blocks=-1),  # only 0, 1, 3, 4, 7 and 9 exist
     dict(prefill_k_split=4), dict(prefill_k_split=-1),
 ])
 def test_constraint_violations_are_refused_and_change_nothing(bad):
@@ -72,11 +72,11 @@ def test_tiling_enters_the_plans():
     # the integer prefill kernel: chosen per call (a short token range: the 128 x 128 kernel; long ones: the kernel that
     # dequantizes in registers, with the token tile that fills 256 units best), or forced
     tman.tman_set_tiling(tman.tman_default_tiling())
-    assert tman.tman_mpgemm_i8_token_blocks(pre, 256) == 1
+    assert tman.tman_mpgemm_i8_token_blocks(pre, 256) == 9
     assert tman.tman_mpgemm_i8_token_blocks(pre, 1024) in (3, 4, 7)
     assert tman.tman_mpgemm_i8_token_blocks(tman.Shape(256, 512, 4, 64), 128) == 1
     assert tman.tman_mpgemm_i8_token_blocks(tman.Shape(256, 500, 4, 64), 128) == 0
-    for forced in (1, 3, 4, 7):
+    for forced in (1, 3, 4, 7, 9):
         tman.tman_set_tiling(_with(i8_token_blocks=forced))
         assert tman.tman_mpgemm_i8_token_blocks(pre, 1024) == forced
         assert tman.tman_mpgemm_i8_token_blocks(pre, 5) == forced
