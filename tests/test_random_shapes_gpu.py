@@ -29,6 +29,30 @@ def test_random_shapes(oracle_lib, block):
         assert np.isfinite(err) and err <= TOL, f"{('mpgemv', 'mpgemv_x', 'mpgemm')[kind]} {shape} N={N}: {err:.3e}"
 
 
+@pytest.mark.parametrize("mode", [2, 3])
+def test_random_shapes_through_the_k_split_prefill_kernel(oracle_lib, mode):
+    """The same sweep for the prefill kernel whose waves split K, which the launcher only picks for long K on small
+    grids: forced here (tiling.prefill_k_split) for random shapes with its 64 x 256 (2) and 128 x 128 (3) tile."""
+    t = tman.tman_default_tiling()
+    t.prefill_k_split = mode
+    tman.tman_set_tiling(t)
+    try:
+        rng = np.random.default_rng(2511_11248 + 10 * mode)
+        for it in range(16):
+            bits, group, hz = FORMATS[rng.integers(len(FORMATS))]
+            M = int(rng.integers(33, 500))
+            K = group * int(rng.integers(1, 5000 // group))
+            N = int(rng.integers(33, 420))
+            q, s, z, x = rand_case(70000 + 100 * mode + it, M, K, N, bits, group, hz)
+            shape = tman.Shape(M, K, bits, group, hz)
+            assert tman.tman_mpgemm_splits_k(shape, N) == 1
+            y = mpgemm(shape, pack(shape, q, s, z), x)
+            err = oracle.row_relative_error(y, oracle.matmul(q, s, z, x, bits, group)).max()
+            assert np.isfinite(err) and err <= TOL, f"k split {mode} {shape} N={N}: {err:.3e}"
+    finally:
+        tman.tman_set_tiling(tman.tman_default_tiling())
+
+
 def test_ternary_weights_with_one_scale_per_tensor(oracle_lib):
     """The paper's BitNet configuration (Sec. 6.1: ternary weights treated as 2-bit, one scale per tensor; kernel
     shapes 2560 / 6912) expressed in the group format: codes in {0, 1, 2}, zero = 1, every group the same scale.
