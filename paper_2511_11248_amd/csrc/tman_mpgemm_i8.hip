@@ -110,10 +110,87 @@ __global__ void __launch_bounds__(256) quantize_act_i8_kernel(const uint16_t* __
     }
 }
 
+// The same for activations that start on a 16-byte boundary (every row then does: K is a multiple of 32): thread t
+// reads group t of the token (32 columns, 64 bytes) once, with four 16-byte loads, and keeps it in registers from
+// the search for the maximum to the rounding; only tokens longer than 8192 columns read their further groups twice.
+__global__ void __launch_bounds__(256) quantize_act_i8_aligned_kernel(const uint16_t* __restrict__ x, int K,
+                                                                      int8_t* __restrict__ q, float* __restrict__ absmax,
+                                                                      int32_t* __restrict__ sums) {
+    __shared__ unsigned wave_max[4];
+    __shared__ int wave_sum[4];
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const uint16_t* xb = x + (size_t)n * K;
+    const int n_groups = K / 32;
+    auto load_group = [&](u32x4 (&c)[4], int g) {
+        const u32x4* src = reinterpret_cast<const u32x4*>(xb + (size_t)g * 32);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c[i] = src[i];
+    };
+    auto group_max = [&](const u32x4 (&c)[4], unsigned mx) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mx = max(mx, max(c[i][e] & 0x7fffu, (c[i][e] >> 16) & 0x7fffu));
+        return mx;
+    };
+    u32x4 mine[4] = {};
+    const bool have = tid < n_groups;
+    if (have) load_group(mine, tid);
+    unsigned mx = group_max(mine, 0u);  // magnitudes compare like their bit patterns
+    for (int g = tid + 256; g < n_groups; g += 256) {
+        u32x4 c[4];
+        load_group(c, g);
+        mx = group_max(c, mx);
+    }
+    for (int d = 1; d < 64; d <<= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, d, 64));
+    if ((tid & 63) == 0) wave_max[tid >> 6] = mx;
+    __syncthreads();
+    mx = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+    const float amax = (float)__builtin_bit_cast(_Float16, (uint16_t)mx);
+    // the decision is taken in binary32: one correctly rounded division, one product, round to nearest even
+    const float inv = amax > 0.f ? __fdiv_rn(127.0f, amax) : 0.f;
+    int s = 0;
+    auto quantize_group = [&](const u32x4 (&c)[4], int g) {
+        int v[32];
+#pragma unroll
+        for (int col = 0; col < 32; ++col) {
+            const uint32_t word = c[col >> 3][(col >> 1) & 3];
+            const uint16_t bits = (uint16_t)((col & 1) ? word >> 16 : word);
+            v[col] = (int)rintf(__fmul_rn((float)__builtin_bit_cast(_Float16, bits), inv));
+            s += v[col];
+        }
+        u32x4 out[2];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) w |= (uint32_t)(v[sigma(4 * i + b)] & 0xff) << (8 * b);
+            out[i >> 2][i & 3] = w;
+        }
+        u32x4* dst = reinterpret_cast<u32x4*>(q + (size_t)n * K + (size_t)g * 32);
+        dst[0] = out[0];
+        dst[1] = out[1];
+    };
+    if (have) quantize_group(mine, tid);
+    for (int g = tid + 256; g < n_groups; g += 256) {
+        u32x4 c[4];
+        load_group(c, g);
+        quantize_group(c, g);
+    }
+    for (int d = 1; d < 64; d <<= 1) s += __shfl_xor(s, d, 64);
+    if ((tid & 63) == 0) wave_sum[tid >> 6] = s;
+    __syncthreads();
+    if (tid == 0) {
+        absmax[n] = amax;
+        sums[n] = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
+    }
+}
+
 int launch_quantize_act_i8(const void* x, int N, int K, void* out, hipStream_t st) {
     const ActI8Layout l = act_i8_layout(N, K);
     uint8_t* o = static_cast<uint8_t*>(out);
-    hipLaunchKernelGGL(quantize_act_i8_kernel, dim3((unsigned)N), dim3(256), 0, st, static_cast<const uint16_t*>(x), K,
+    const auto kernel = (reinterpret_cast<uintptr_t>(x) & 15u) == 0 ? quantize_act_i8_aligned_kernel : quantize_act_i8_kernel;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)N), dim3(256), 0, st, static_cast<const uint16_t*>(x), K,
                        reinterpret_cast<int8_t*>(o), reinterpret_cast<float*>(o + l.absmax_off),
                        reinterpret_cast<int32_t*>(o + l.sum_off));
     return launch_status();

@@ -26,11 +26,17 @@ def _case(seed, M, K, N, bits, hz, group):
     return q, rs, rz, s, z, x
 
 
-def _quantize(x):
+def _quantize(x, misalign=False):
     N, K = x.shape
     buf = torch.empty(tman.tman_act_i8_bytes(N, K), dtype=torch.uint8, device=dev())
     buf.fill_(0x5A)
-    tman.tman_quantize_act_i8(to_dev(x), N, K, buf)
+    xd = to_dev(x)
+    if misalign:  # the activations start 2 bytes past a 16-byte boundary: the kernel without wide loads
+        big = torch.empty(N * K + 8, dtype=torch.float16, device=dev())
+        big[1:1 + N * K] = xd.reshape(-1)
+        xd = big[1:1 + N * K].view(N, K)
+        assert xd.data_ptr() % 16 == 2
+    tman.tman_quantize_act_i8(xd, N, K, buf)
     return buf
 
 
@@ -44,14 +50,16 @@ def _read_buffer(buf, N, K):
     return xq.reshape(N, K), b[qb:qb + N * 4].view(np.float32), b[qb + nb:qb + nb + N * 4].view(np.int32)
 
 
-@pytest.mark.parametrize("N,K,gain", [(1, 32, 1.0), (5, 2560, 1.0), (130, 6912, 1.0), (3, 96, 200.0), (4, 512, 1e-3)])
-def test_quantizer_matches_the_oracle_bit_for_bit(oracle_lib, N, K, gain):
+@pytest.mark.parametrize("misalign", [False, True])
+@pytest.mark.parametrize("N,K,gain", [(1, 32, 1.0), (5, 2560, 1.0), (130, 6912, 1.0), (3, 96, 200.0), (4, 512, 1e-3),
+                                      (3, 8192 + 96, 1.0)])  # more than 256 groups of 32 columns per token
+def test_quantizer_matches_the_oracle_bit_for_bit(oracle_lib, N, K, gain, misalign):
     x = (synth.normal_fp16(40 + N + K, N * K).astype(np.float64) * gain).astype(np.float16).reshape(N, K)
     if N > 2:
         x[2, :] = 0
         x[1, :8] = [127, -63.5, 1.5, 2.5, 0.25, -127, 0.5, -0.5]  # exact ties when the token's largest is 127
         x[1, 8:] = np.clip(x[1, 8:], -100, 100)
-    xq, mx, sums = _read_buffer(_quantize(x), N, K)
+    xq, mx, sums = _read_buffer(_quantize(x, misalign), N, K)
     xo, mo = oracle.quantize_activations_i8(x)
     assert np.array_equal(mx, mo)
     assert np.array_equal(xq, xo)
